@@ -1,0 +1,165 @@
+/*
+ * sjd.h - C boundary of the MI355X (gfx950) library for selective Jacobi decoding: the inverse
+ * (sampling) pass of a block-autoregressive normalizing flow whose conditioner is a causal
+ * transformer.
+ *
+ * Vocabulary.  T tokens per sample (the paper's L), D values per token, K flow blocks, N
+ * transformer layers per block, W width, H heads, B batch.  Blocks are numbered in SAMPLING
+ * order: block 0 is the first one applied to the latent (the paper's "first (K-th) layer",
+ * Sec. 3.5).  For a block with input y (the paper's z_{k+1}) and output x (z_k), per token l:
+ *     x_1 = y_1,    x_l = y_l * exp(alpha_l) + mu_l,    (mu, alpha)_l = conditioner(x_<l),
+ * which is eq. 5 with mu = g_k and alpha = -s_k.  The conditioner sees tokens strictly before l.
+ * Bit j of sjd_config.reverse_mask makes block j work on the reversed token order (the
+ * permutation mentioned below eq. 4); data crossing this boundary is always in canonical order.
+ *
+ * Memory.  Every pointer named *_dev is DEVICE memory owned by the caller (contiguous float32
+ * [batch, T, D]); pointers named *_host are HOST memory owned by the caller.  The library neither
+ * frees nor keeps them.  z_dev and x_dev must not overlap.  The handle owns the weights, the
+ * key/value cache and all workspaces, sized at creation for max_batch.
+ *
+ * Streams.  `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  All work
+ * is enqueued on it.  Calls that run Jacobi decoding read one integer per pass back to the host
+ * (the number of samples still iterating) and therefore synchronise that stream; all calls
+ * return with their outputs complete.  One handle must not be used from two threads at once.
+ *
+ * Errors.  Every int-returning call gives SJD_OK (0) or a negative code; nothing throws or aborts
+ * across this boundary.  sjd_last_error() returns a thread-local description of the last failure.
+ *
+ * This library has no CPU path: every step runs in HIP kernels, and creation fails with SJD_EHIP
+ * when no gfx950 device is usable.
+ */
+#ifndef SJD_H
+#define SJD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SJD_OK 0
+#define SJD_EINVAL (-1)     /* null pointer, bad shape, batch > max_batch, NaN tau, bad block index ... */
+#define SJD_ENOMEM (-2)     /* host or device allocation failed */
+#define SJD_EHIP (-3)       /* a HIP call failed; see sjd_last_error() */
+#define SJD_ENONFINITE (-4) /* a sample's iterate difference was NaN/Inf when its loop ended; outputs are written */
+#define SJD_ESTATE (-5)     /* weights not loaded yet */
+
+#define SJD_MAX_BLOCKS 32
+
+#define SJD_DTYPE_F32 0  /* everything float32 (correctness configuration) */
+#define SJD_DTYPE_BF16 1 /* bf16 weights, matrix operands, stored activations and KV cache; float32 state
+                            (x, mu, alpha), residual stream, LayerNorm statistics, softmax, accumulators, delta */
+
+#if defined(__GNUC__)
+#define SJD_API __attribute__((visibility("default")))
+#else
+#define SJD_API
+#endif
+
+typedef struct sjd_flow sjd_flow; /* opaque */
+
+typedef struct {
+    int32_t n_blocks;   /* K, 1..SJD_MAX_BLOCKS */
+    int32_t n_layers;   /* N >= 1 */
+    int32_t width;      /* W, a multiple of n_heads; bf16 mode needs W % 64 == 0 */
+    int32_t n_heads;    /* H */
+    int32_t mlp_ratio;  /* hidden = mlp_ratio * W */
+    int32_t seq_len;    /* T >= 1 */
+    int32_t token_dim;  /* D >= 1 */
+    int32_t max_batch;  /* largest batch any call will pass */
+    int32_t dtype;      /* SJD_DTYPE_* */
+    uint32_t reverse_mask;
+} sjd_config;
+
+/* Options of Jacobi decoding (Sec. 3.3, Alg. 1). */
+typedef struct {
+    float tau;              /* stop a sample when its delta < tau (strict).  tau = 0 runs to the cap. */
+    int32_t criterion;      /* 0: delta = mean over (l, d) of |x^t - x^(t-1)|;  1: the maximum (Alg. 1 as printed) */
+    int32_t init;           /* 0: x^0 = 0 (Alg. 1);  1: x^0 = the block's input (Sec. 4.3, initialisation study) */
+    int32_t max_iters;      /* 0 or >= T: the cap is T (Prop. 3.2: the T-th iterate is exact); else a lower cap */
+    int32_t drop_converged; /* 1: converged samples leave the batch the conditioner runs on;  0: they stay
+                               (and are ignored).  Results and counts are the same either way. */
+} sjd_jacobi_opts;
+
+typedef struct {
+    int32_t block_iters[SJD_MAX_BLOCKS];     /* conditioner passes launched (max over samples); T-1 for a sequential block */
+    float mean_sample_iters[SJD_MAX_BLOCKS]; /* mean over samples of each sample's own pass count */
+    float block_ms[SJD_MAX_BLOCKS];          /* device time of the block, from events on the stream */
+} sjd_stats;
+
+/* Timing of kernel families inside the library (for roofline reports).  Off by default. */
+#define SJD_PROF_GEMM 0        /* all dense projections of whole-sequence passes */
+#define SJD_PROF_ATTENTION 1   /* whole-sequence causal attention */
+#define SJD_PROF_EPILOGUE 2    /* fused affine update / difference reduction / convergence */
+#define SJD_PROF_DECODE_GEMM 3 /* projections of single-token steps */
+#define SJD_PROF_DECODE_ATTN 4 /* KV-cached single-token attention */
+#define SJD_PROF_OTHER 5       /* embedding, LayerNorm, ... */
+#define SJD_PROF_FAMILIES 6
+typedef struct {
+    double ms[SJD_PROF_FAMILIES];       /* summed device time per family since the last reset */
+    int64_t launches[SJD_PROF_FAMILIES];
+    double flops[SJD_PROF_FAMILIES];    /* algorithmic flops of those launches (2*M*N*K, causal attention counted on the lower triangle) */
+    double bytes[SJD_PROF_FAMILIES];    /* algorithmic bytes: operands read once + results written once */
+} sjd_profile;
+
+/* Creates a flow for `cfg` on the current HIP device and allocates every buffer it will need.
+ * *out receives the handle.  SJD_EINVAL for shapes outside the limits stated at sjd_config. */
+SJD_API int sjd_flow_create(const sjd_config *cfg, sjd_flow **out);
+
+/* "Load flow weights": copies the functions s_k, g_k of every block (Alg. 1, Input) to the device.
+ * host_blob is HOST memory: K blocks in sampling order, each a run of little-endian float32
+ * tensors, matrices row-major [in, out]:
+ *     w_in [D,W]  b_in [W]  pos [T,W]
+ *     N x { ln1_g [W] ln1_b [W]  w_qkv [W,3W] b_qkv [3W]  w_o [W,W] b_o [W]
+ *           ln2_g [W] ln2_b [W]  w_fc1 [W,R*W] b_fc1 [R*W]  w_fc2 [R*W,W] b_fc2 [W] }
+ *     lnf_g [W] lnf_b [W]  w_head [W,2D] b_head [2D]          (head columns: [mu | alpha])
+ * q, k, v are the three W-wide column groups of w_qkv; head h owns columns h*dh..(h+1)*dh of each.
+ * nbytes must equal the size that layout implies, else SJD_EINVAL.  In bf16 mode matrices are
+ * rounded to bf16 (nearest even) on load.  The blob is not referenced after the call returns. */
+SJD_API int sjd_flow_load_weights(sjd_flow *flow, const void *host_blob, size_t nbytes);
+
+/* Jacobi decoding of block `block` (Sec. 3.3, Alg. 1; iteration map of App. B, Def. A.1):
+ * x^0 per opts->init, then x^t = F(x^(t-1)) for all tokens at once, each sample stopping by its own
+ * delta (see sjd_jacobi_opts) or at the cap.  z_dev: the block's input; x_dev: receives each
+ * sample's newest iterate.  iters_per_sample_host (nullable, [batch]): passes each sample took,
+ * counting the last one.  block_iters_host (nullable): passes launched.  SJD_ENONFINITE if a
+ * sample ended with a non-finite delta. */
+SJD_API int sjd_jacobi_inverse_block(sjd_flow *flow, int block, const float *z_dev, float *x_dev, int batch,
+                             const sjd_jacobi_opts *opts, int32_t *iters_per_sample_host,
+                             int32_t *block_iters_host, void *hip_stream);
+
+/* Sequential inverse of block `block` (Sec. 3.1, eq. 5) with a key/value cache (Sec. 3.5):
+ * T-1 single-token conditioner steps. */
+SJD_API int sjd_sequential_inverse_block(sjd_flow *flow, int block, const float *z_dev, float *x_dev, int batch,
+                                 void *hip_stream);
+
+/* The whole cascade x = f_0(...f_{K-1}(z_K)) (Sec. 3.1, eq. 2) with a per-block mode (Sec. 3.5):
+ * bit j of jacobi_mask set => block j by Jacobi decoding, clear => sequentially.  ~1u is the
+ * selective strategy, 0 the sequential baseline, ~0u Jacobi everywhere.  stats_host (nullable) and
+ * iters_host (nullable, [K][batch] passes per block and sample) are filled on return. */
+SJD_API int sjd_sample(sjd_flow *flow, const float *z_dev, float *x_dev, int batch, uint32_t jacobi_mask,
+               const sjd_jacobi_opts *opts, sjd_stats *stats_host, int32_t *iters_host, void *hip_stream);
+
+/* One whole-sequence conditioner pass of block `block` on x_dev [batch, T, D] (canonical order):
+ * mu_dev, alpha_dev [batch, T, D] receive the parameters of every token computed from the tokens
+ * before it (zeros for the first processed token).  This is s_k, g_k of eq. 5 evaluated for all l
+ * at once, i.e. the inside of F (Def. A.1); exported so that it can be checked on its own. */
+SJD_API int sjd_conditioner(sjd_flow *flow, int block, const float *x_dev, float *mu_dev, float *alpha_dev, int batch,
+                    void *hip_stream);
+
+/* Kernel-family timing: when enabled, every launch of the selected families (bit f of
+ * family_mask = SJD_PROF_* f) is bracketed by events on the caller's stream.  Costs a little time per launch. */
+SJD_API int sjd_profile_enable(sjd_flow *flow, uint32_t family_mask);
+SJD_API int sjd_profile_read(sjd_flow *flow, sjd_profile *out_host, int reset);
+
+/* Device bytes held by the handle (weights + cache + workspaces). */
+SJD_API size_t sjd_flow_device_bytes(const sjd_flow *flow);
+
+SJD_API const char *sjd_last_error(void);
+SJD_API void sjd_flow_destroy(sjd_flow *flow);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SJD_H */

@@ -1,0 +1,212 @@
+"""Thin Python binding of the HIP library ``libsjd.so`` (see ``include/sjd.h``).
+
+Argument marshalling only: every step of selective Jacobi decoding runs in the library's kernels.
+PyTorch is used for device memory and streams.  There is no CPU path: importing works anywhere,
+but creating a ``Flow`` without the built library or without an MI355X raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsjd.so")
+
+SJD_OK, SJD_EINVAL, SJD_ENOMEM, SJD_EHIP, SJD_ENONFINITE, SJD_ESTATE = 0, -1, -2, -3, -4, -5
+SJD_MAX_BLOCKS = 32
+DTYPE_F32, DTYPE_BF16 = 0, 1
+PROF_GEMM, PROF_ATTENTION, PROF_EPILOGUE, PROF_DECODE_GEMM, PROF_DECODE_ATTN, PROF_OTHER = range(6)
+PROF_FAMILIES = 6
+PROF_NAMES = ("gemm", "attention", "epilogue", "decode_gemm", "decode_attn", "other")
+
+EXPORTS = ("sjd_flow_create", "sjd_flow_load_weights", "sjd_jacobi_inverse_block", "sjd_sequential_inverse_block",
+           "sjd_sample", "sjd_conditioner", "sjd_profile_enable", "sjd_profile_read", "sjd_flow_device_bytes",
+           "sjd_last_error", "sjd_flow_destroy")
+
+
+class SjdConfig(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_blocks", "n_layers", "width", "n_heads", "mlp_ratio", "seq_len",
+                                         "token_dim", "max_batch", "dtype")] + [("reverse_mask", C.c_uint32)]
+
+
+class SjdJacobiOpts(C.Structure):
+    _fields_ = [("tau", C.c_float), ("criterion", C.c_int32), ("init", C.c_int32), ("max_iters", C.c_int32),
+                ("drop_converged", C.c_int32)]
+
+
+class SjdStats(C.Structure):
+    _fields_ = [("block_iters", C.c_int32 * SJD_MAX_BLOCKS), ("mean_sample_iters", C.c_float * SJD_MAX_BLOCKS),
+                ("block_ms", C.c_float * SJD_MAX_BLOCKS)]
+
+
+class SjdProfile(C.Structure):
+    _fields_ = [("ms", C.c_double * PROF_FAMILIES), ("launches", C.c_int64 * PROF_FAMILIES),
+                ("flops", C.c_double * PROF_FAMILIES), ("bytes", C.c_double * PROF_FAMILIES)]
+
+
+class SjdError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"sjd error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """Loads libsjd.so; raises if it has not been built (there is no fallback)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2505_24791_amd.build` "
+                           "(or __graft_entry__.build()) first; this package has no CPU fallback")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32p, fp = C.c_void_p, C.POINTER(C.c_int32), C.c_void_p
+    lib.sjd_flow_create.argtypes = [C.POINTER(SjdConfig), C.POINTER(vp)]
+    lib.sjd_flow_load_weights.argtypes = [vp, vp, C.c_size_t]
+    lib.sjd_jacobi_inverse_block.argtypes = [vp, C.c_int, fp, fp, C.c_int, C.POINTER(SjdJacobiOpts), i32p, i32p, vp]
+    lib.sjd_sequential_inverse_block.argtypes = [vp, C.c_int, fp, fp, C.c_int, vp]
+    lib.sjd_sample.argtypes = [vp, fp, fp, C.c_int, C.c_uint32, C.POINTER(SjdJacobiOpts), C.POINTER(SjdStats), i32p, vp]
+    lib.sjd_conditioner.argtypes = [vp, C.c_int, fp, fp, fp, C.c_int, vp]
+    lib.sjd_profile_enable.argtypes = [vp, C.c_uint32]
+    lib.sjd_profile_read.argtypes = [vp, C.POINTER(SjdProfile), C.c_int]
+    lib.sjd_flow_device_bytes.argtypes = [vp]
+    lib.sjd_flow_device_bytes.restype = C.c_size_t
+    lib.sjd_last_error.restype = C.c_char_p
+    lib.sjd_flow_destroy.argtypes = [vp]
+    lib.sjd_flow_destroy.restype = None
+    for name in EXPORTS:
+        if name not in ("sjd_flow_device_bytes", "sjd_last_error", "sjd_flow_destroy"):
+            getattr(lib, name).restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def _check(rc: int, allow_nonfinite: bool = False) -> int:
+    if rc == SJD_OK or (allow_nonfinite and rc == SJD_ENONFINITE):
+        return rc
+    raise SjdError(rc, load_library().sjd_last_error().decode())
+
+
+@dataclass
+class JacobiOpts:
+    tau: float = 1e-3
+    criterion: int = 0
+    init: int = 0
+    max_iters: int = 0
+    drop_converged: int = 1
+
+    def c(self) -> SjdJacobiOpts:
+        return SjdJacobiOpts(self.tau, self.criterion, self.init, self.max_iters, self.drop_converged)
+
+
+def _stream_ptr() -> Optional[int]:
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t, shape=None) -> C.c_void_p:
+    import torch
+    assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous(), "need a contiguous float32 CUDA tensor"
+    if shape is not None:
+        assert tuple(t.shape) == tuple(shape), (tuple(t.shape), tuple(shape))
+    return C.c_void_p(t.data_ptr())
+
+
+class Flow:
+    """A flow on the current device.  ``cfg`` needs the attributes of ``workloads.FlowConfig``."""
+
+    def __init__(self, cfg, max_batch: Optional[int] = None, dtype: Optional[int] = None):
+        self.lib = load_library()
+        self.cfg = cfg
+        self.max_batch = int(max_batch if max_batch is not None else cfg.batch)
+        self.dtype = (DTYPE_BF16 if cfg.bf16 else DTYPE_F32) if dtype is None else dtype
+        c = SjdConfig(cfg.n_blocks, cfg.n_layers, cfg.width, cfg.n_heads, cfg.mlp_ratio, cfg.seq_len, cfg.token_dim,
+                      self.max_batch, self.dtype, cfg.reverse_mask)
+        h = C.c_void_p()
+        _check(self.lib.sjd_flow_create(C.byref(c), C.byref(h)))
+        self._h = h
+
+    def close(self) -> None:
+        if getattr(self, "_h", None):
+            self.lib.sjd_flow_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def device_bytes(self) -> int:
+        return int(self.lib.sjd_flow_device_bytes(self._h))
+
+    def load_weights(self, blob: np.ndarray) -> None:
+        blob = np.ascontiguousarray(blob, dtype=np.float32)
+        _check(self.lib.sjd_flow_load_weights(self._h, C.c_void_p(blob.ctypes.data), blob.nbytes))
+
+    def _shape(self, batch):
+        return (batch, self.cfg.seq_len, self.cfg.token_dim)
+
+    def conditioner(self, block: int, x):
+        import torch
+        B = x.shape[0]
+        mu = torch.empty_like(x); al = torch.empty_like(x)
+        _check(self.lib.sjd_conditioner(self._h, block, _dev(x, self._shape(B)), _dev(mu), _dev(al), B, _stream_ptr()))
+        return mu, al
+
+    def jacobi_inverse_block(self, block: int, z, opts: JacobiOpts, allow_nonfinite: bool = False):
+        """Returns (x, iters_per_sample int32 [B], passes_launched, rc)."""
+        import torch
+        B = z.shape[0]
+        x = torch.empty_like(z)
+        iters = np.zeros(B, np.int32)
+        passes = C.c_int32(0)
+        o = opts.c()
+        rc = _check(self.lib.sjd_jacobi_inverse_block(self._h, block, _dev(z, self._shape(B)), _dev(x), B, C.byref(o),
+                                                      iters.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(passes),
+                                                      _stream_ptr()), allow_nonfinite)
+        return x, iters, int(passes.value), rc
+
+    def sequential_inverse_block(self, block: int, z):
+        import torch
+        B = z.shape[0]
+        x = torch.empty_like(z)
+        _check(self.lib.sjd_sequential_inverse_block(self._h, block, _dev(z, self._shape(B)), _dev(x), B, _stream_ptr()))
+        return x
+
+    def sample(self, z, jacobi_mask: int, opts: JacobiOpts, out=None, want_iters: bool = True,
+               allow_nonfinite: bool = False):
+        """Returns (x, stats dict, iters int32 [K, B] or None)."""
+        import torch
+        B = z.shape[0]
+        x = torch.empty_like(z) if out is None else out
+        K = self.cfg.n_blocks
+        stats = SjdStats()
+        iters = np.zeros((K, B), np.int32) if want_iters else None
+        ip = iters.ctypes.data_as(C.POINTER(C.c_int32)) if want_iters else None
+        o = opts.c()
+        _check(self.lib.sjd_sample(self._h, _dev(z, self._shape(B)), _dev(x, self._shape(B)), B,
+                                   C.c_uint32(jacobi_mask & 0xFFFFFFFF), C.byref(o), C.byref(stats), ip, _stream_ptr()),
+               allow_nonfinite)
+        st = {"block_iters": list(stats.block_iters[:K]), "mean_sample_iters": list(stats.mean_sample_iters[:K]),
+              "block_ms": list(stats.block_ms[:K])}
+        return x, st, iters
+
+    def profile_enable(self, families) -> None:
+        mask = 0
+        for f in families:
+            mask |= 1 << f
+        _check(self.lib.sjd_profile_enable(self._h, mask))
+
+    def profile_read(self, reset: bool = True) -> dict:
+        p = SjdProfile()
+        _check(self.lib.sjd_profile_read(self._h, C.byref(p), 1 if reset else 0))
+        return {PROF_NAMES[i]: {"ms": p.ms[i], "launches": int(p.launches[i]), "flops": p.flops[i], "bytes": p.bytes[i]}
+                for i in range(PROF_FAMILIES)}

@@ -1,0 +1,270 @@
+// Causal multi-head attention.
+//
+//  * attention_rows_kernel: one wave per (sample, head, query row), any head size and sequence
+//    length, float32 or bf16 storage, float32 arithmetic.  It serves the float32 configuration's
+//    whole-sequence passes and, with a key/value cache, every single-token step of the sequential
+//    inverse (Sec. 3.5), where it is bound by reading the cached prefix from HBM.
+//  * flash_attention_bf16_kernel: whole-sequence causal attention for head size 64 on bf16 with
+//    MFMA; K tiles and transposed V tiles are staged in LDS, scores never leave registers
+//    (online softmax in float32), so there is no T x T buffer.
+#include "common.h"
+
+namespace sjd {
+
+// ------------------------------------------------------------------------------------------------
+// Row-wise kernel.  Keys 0..n_cached-1 come from the cache; if `fresh` is set the query's own
+// position (key n_cached) comes from the row just computed, and that row's k, v are also written
+// into the cache at position n_cached.
+template <typename QT, typename KVT>
+__global__ __launch_bounds__(256) void attention_rows_kernel(const QT *__restrict__ q, int64_t q_stride,
+                                                             const KVT *k, const KVT *v, int64_t kv_stride,
+                                                             int64_t kv_sample_stride, const QT *__restrict__ kfresh,
+                                                             const QT *__restrict__ vfresh, KVT *kstore, KVT *vstore,
+                                                             QT *__restrict__ o, int64_t o_stride, int n_work,
+                                                             int q_rows_per_sample, int t0, int H, int dh,
+                                                             int max_keys) {
+    extern __shared__ float smem[];
+    const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int w = blockIdx.x * 4 + wv;
+    if (w >= n_work) return;
+    float *qs = smem + (size_t)wv * (dh + max_keys);
+    float *sc = qs + dh;
+    const int r = w % q_rows_per_sample;
+    const int h = (w / q_rows_per_sample) % H;
+    const int i = w / (q_rows_per_sample * H);
+    const int64_t qrow = (int64_t)i * q_rows_per_sample + r;
+    const int n_cached = kfresh ? t0 + r : t0 + r + 1;
+    const int n_keys = t0 + r + 1;
+    const QT *qp = q + qrow * q_stride + h * dh;
+    for (int d = lane; d < dh; d += 64) qs[d] = to_f32<QT>(qp[d]);
+    const KVT *kb = k + (int64_t)i * kv_sample_stride + h * dh;
+    const KVT *vb = v + (int64_t)i * kv_sample_stride + h * dh;
+    const QT *kf = kfresh ? kfresh + qrow * q_stride + h * dh : nullptr;
+    const QT *vf = vfresh ? vfresh + qrow * q_stride + h * dh : nullptr;
+    if (kf) {
+        KVT *ks = kstore + (int64_t)i * kv_sample_stride + (int64_t)n_cached * kv_stride + h * dh;
+        KVT *vs = vstore + (int64_t)i * kv_sample_stride + (int64_t)n_cached * kv_stride + h * dh;
+        for (int d = lane; d < dh; d += 64) {
+            ks[d] = from_f32<KVT>(to_f32<QT>(kf[d]));
+            vs[d] = from_f32<KVT>(to_f32<QT>(vf[d]));
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): this wave's LDS writes of q are visible to its lanes
+    const float scale = 1.0f / sqrtf((float)dh);
+    float mx = -INFINITY;
+    for (int s = lane; s < n_keys; s += 64) {
+        float dot = 0.f;
+        if (s < n_cached) {
+            const KVT *kr = kb + (int64_t)s * kv_stride;
+            for (int d = 0; d < dh; ++d) dot = fmaf(qs[d], to_f32<KVT>(kr[d]), dot);
+        } else {
+            for (int d = 0; d < dh; ++d) dot = fmaf(qs[d], to_f32<QT>(kf[d]), dot);
+        }
+        dot *= scale;
+        sc[s] = dot;
+        mx = fmaxf(mx, dot);
+    }
+    mx = wave_max(mx);
+    float den = 0.f;
+    for (int s = lane; s < n_keys; s += 64) {
+        const float e = expf(sc[s] - mx);
+        sc[s] = e;
+        den += e;
+    }
+    den = wave_sum(den);
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_s_waitcnt(0xc07f);
+    const float inv = 1.0f / den;
+    for (int d = lane; d < dh; d += 64) {
+        float acc = 0.f;
+        for (int s = 0; s < n_cached; ++s) acc = fmaf(sc[s], to_f32<KVT>(vb[(int64_t)s * kv_stride + d]), acc);
+        if (n_cached < n_keys) acc = fmaf(sc[n_cached], to_f32<QT>(vf[d]), acc);
+        o[qrow * o_stride + h * dh + d] = from_f32<QT>(acc * inv);
+    }
+}
+
+template <typename QT, typename KVT>
+void launch_attention_rows(const QT *q, int64_t q_stride, const KVT *k, const KVT *v, int64_t kv_stride,
+                           int64_t kv_sample_stride, QT *o, int64_t o_stride, int n_samples, int q_rows_per_sample,
+                           int t0, int H, int dh, hipStream_t s) {
+    const int n_work = n_samples * H * q_rows_per_sample;
+    if (n_work <= 0) return;
+    const int max_keys = t0 + q_rows_per_sample;
+    const size_t smem = 4 * (size_t)(dh + max_keys) * sizeof(float);
+    hipLaunchKernelGGL((attention_rows_kernel<QT, KVT>), dim3((n_work + 3) / 4), dim3(256), smem, s, q, q_stride, k, v,
+                       kv_stride, kv_sample_stride, (const QT *)nullptr, (const QT *)nullptr, (KVT *)nullptr,
+                       (KVT *)nullptr, o, o_stride, n_work, q_rows_per_sample, t0, H, dh, max_keys);
+}
+template void launch_attention_rows<float, float>(const float *, int64_t, const float *, const float *, int64_t,
+                                                  int64_t, float *, int64_t, int, int, int, int, int, hipStream_t);
+template void launch_attention_rows<bf16, bf16>(const bf16 *, int64_t, const bf16 *, const bf16 *, int64_t, int64_t,
+                                                bf16 *, int64_t, int, int, int, int, int, hipStream_t);
+
+template <typename AT>
+void launch_decode_attention(const AT *qkv, AT *kcache, AT *vcache, AT *o, int B, int T, int t, int H, int dh,
+                             hipStream_t s) {
+    const int n_work = B * H;
+    if (n_work <= 0) return;
+    const int W = H * dh;
+    const int max_keys = t + 1;
+    const size_t smem = 4 * (size_t)(dh + max_keys) * sizeof(float);
+    hipLaunchKernelGGL((attention_rows_kernel<AT, AT>), dim3((n_work + 3) / 4), dim3(256), smem, s, qkv,
+                       (int64_t)3 * W, (const AT *)kcache, (const AT *)vcache, (int64_t)W, (int64_t)T * W,
+                       qkv + W, qkv + 2 * W, kcache, vcache, o, (int64_t)W, n_work, 1, t, H, dh, max_keys);
+}
+template void launch_decode_attention<float>(const float *, float *, float *, float *, int, int, int, int, int,
+                                             hipStream_t);
+template void launch_decode_attention<bf16>(const bf16 *, bf16 *, bf16 *, bf16 *, int, int, int, int, int, hipStream_t);
+
+// ------------------------------------------------------------------------------------------------
+// Flash-style kernel, head size 64.  A workgroup (4 waves) owns 128 query rows of one
+// (sample, head); a wave owns 32 of them.  The score block is computed transposed,
+// S^T = K Q^T, so that a lane holds one query column: row statistics of the online softmax are
+// lane-local plus one cross-half exchange, and the probabilities are already laid out as the
+// B operand of the second product O^T = V^T P^T (16 keys per instruction).
+constexpr int FA_BQ = 128, FA_BK = 64, FA_DH = 64;
+constexpr int FA_KS = FA_DH + 8;   // K tile row stride (bf16)
+constexpr int FA_VS = FA_BK + 8;   // V^T tile row stride (bf16)
+
+__global__ __launch_bounds__(256) void flash_attention_bf16_kernel(const bf16 *__restrict__ qkv, bf16 *__restrict__ o,
+                                                                   int T, int H, float scale_log2) {
+    __shared__ __attribute__((aligned(16))) bf16 Ks[FA_BK * FA_KS];
+    __shared__ __attribute__((aligned(16))) bf16 Vt[FA_DH * FA_VS];
+    const int W = H * FA_DH;
+    const int n_qt = (T + FA_BQ - 1) / FA_BQ;
+    const int qt = n_qt - 1 - (int)blockIdx.x;  // heavy tiles first
+    const int h = blockIdx.y, i = blockIdx.z;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, g = lane >> 5;
+    const bf16 *base = qkv + (size_t)i * T * 3 * W;
+    const int q0 = qt * FA_BQ + wave * 32;      // first query row of this wave
+    const int qrow = q0 + l32;                  // this lane's query row
+    const int qrow_c = qrow < T ? qrow : T - 1;
+
+    // Q^T as B operand: lane (q = l32, g) holds Q[q][16c + 8g .. +7] for the four 16-wide chunks of dh
+    bf16x8 qf[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+        qf[c] = *reinterpret_cast<const bf16x8 *>(base + (size_t)qrow_c * 3 * W + h * FA_DH + 16 * c + 8 * g);
+
+    f32x16 oacc[2];
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) oacc[db][v] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    const int last_row = min(qt * FA_BQ + FA_BQ - 1, T - 1);
+    const int n_kt = last_row / FA_BK + 1;
+    for (int kt = 0; kt < n_kt; ++kt) {
+        const int key0 = kt * FA_BK;
+        __syncthreads();  // previous tile fully consumed
+        // stage K [64 keys][64 d] and V^T [64 d][64 keys]; 512 16-byte chunks each, 2 per thread
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const int c = tid + r * 256;
+            const int key = c >> 3, dc = c & 7;
+            int krow = key0 + key;
+            krow = krow < T ? krow : T - 1;
+            const bf16 *src = base + (size_t)krow * 3 * W + h * FA_DH + dc * 8;
+            const bf16x8 kv8 = *reinterpret_cast<const bf16x8 *>(src + W);
+            const bf16x8 vv8 = *reinterpret_cast<const bf16x8 *>(src + 2 * W);
+            *reinterpret_cast<bf16x8 *>(&Ks[key * FA_KS + dc * 8]) = kv8;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) Vt[(dc * 8 + e) * FA_VS + key] = vv8[e];
+        }
+        __syncthreads();
+        if (key0 > q0 + 31) continue;  // tile lies entirely above this wave's rows (wave-uniform)
+
+        // S^T = K Q^T : two 32-key blocks
+        f32x16 sacc[2];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sacc[kb][v] = 0.f;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(&Ks[(32 * kb + l32) * FA_KS + 16 * c + 8 * g]);
+                sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[c], sacc[kb], 0, 0, 0);
+            }
+        }
+        // register v of block kb is key key0 + 32 kb + 8 (v/4) + 4 g + v%4, query qrow
+        float mx = -INFINITY;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int key = key0 + 32 * kb + 8 * (v >> 2) + 4 * g + (v & 3);
+                float sv = sacc[kb][v] * scale_log2;
+                sv = key <= qrow ? sv : -INFINITY;
+                sacc[kb][v] = sv;
+                mx = fmaxf(mx, sv);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run, mx);
+        // rows past the end of the sequence may see no visible key in a tile; keep them finite
+        const float m_use = m_new == -INFINITY ? 0.f : m_new;
+        const float corr = exp2f(m_run - m_use);
+        float psum = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const float pv = exp2f(sacc[kb][v] - m_use);
+                sacc[kb][v] = pv;
+                psum += pv;
+            }
+        psum += __shfl_xor(psum, 32, 64);
+        l_run = l_run * corr + psum;
+        m_run = m_new;
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) oacc[db][v] *= corr;
+
+        // O^T += V^T P^T, 16 keys per instruction.  Slot e = 4a + b of lane half g stands for key
+        // 32 kb + 16 c2 + 8 a + 4 g + b in both operands.
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int c2 = 0; c2 < 2; ++c2) {
+                bf16x8 pf;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) pf[e] = (bf16)sacc[kb][8 * c2 + e];
+#pragma unroll
+                for (int db = 0; db < 2; ++db) {
+                    const bf16 *vrow = &Vt[(32 * db + l32) * FA_VS + 32 * kb + 16 * c2 + 4 * g];
+                    const bf16x4 lo = *reinterpret_cast<const bf16x4 *>(vrow);
+                    const bf16x4 hi = *reinterpret_cast<const bf16x4 *>(vrow + 8);
+                    bf16x8 vf;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { vf[e] = lo[e]; vf[4 + e] = hi[e]; }
+                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[db], 0, 0, 0);
+                }
+            }
+    }
+    // O^T block db: register v is d = 32 db + 8 (v/4) + 4 g + v%4, query qrow
+    if (qrow < T) {
+        const float inv = 1.0f / l_run;
+        bf16 *orow = o + ((size_t)i * T + qrow) * W + h * FA_DH;
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                bf16x4 ov;
+#pragma unroll
+                for (int b = 0; b < 4; ++b) ov[b] = (bf16)(oacc[db][4 * a + b] * inv);
+                *reinterpret_cast<bf16x4 *>(orow + 32 * db + 8 * a + 4 * g) = ov;
+            }
+    }
+}
+
+void launch_flash_attention_bf16(const bf16 *qkv, bf16 *o, int n_samples, int T, int H, hipStream_t s) {
+    if (n_samples <= 0) return;
+    const int n_qt = (T + FA_BQ - 1) / FA_BQ;
+    const float scale_log2 = 1.4426950408889634f / sqrtf((float)FA_DH);
+    hipLaunchKernelGGL(flash_attention_bf16_kernel, dim3(n_qt, H, n_samples), dim3(256), 0, s, qkv, o, T, H, scale_log2);
+}
+
+}  // namespace sjd

@@ -1,0 +1,123 @@
+// Shared declarations of the HIP library: element types, launchers of every kernel family.
+// gfx950 only (64-wide wavefronts, MFMA, 160 KB LDS per CU).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sjd {
+
+typedef __bf16 bf16;
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+template <typename T> __device__ __forceinline__ float to_f32(T v);
+template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ float to_f32<bf16>(bf16 v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return (bf16)v; }
+
+__device__ __forceinline__ float gelu_erf(float v) { return 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f)); }
+
+// Row -> (sample, token) mapping shared by the embedding and the epilogues.  A whole-sequence pass
+// runs on `rows_per_sample = T` rows per active sample; a single-token step on one row per sample.
+struct RowMap {
+    const int32_t *active;  // [n_rows / rows_per_sample] sample indices, or nullptr for the identity
+    int32_t rows_per_sample;
+    int32_t t0;             // processing-order position of a sample's first row
+    int32_t T;              // tokens per sample
+    int32_t reversed;       // 1: processing position p is canonical token T-1-p
+};
+
+// Epilogue selector of the dense projections.
+enum Epi : int {
+    EPI_BIAS = 0,          // out = acc + bias
+    EPI_BIAS_GELU = 1,     // out = gelu(acc + bias)
+    EPI_BIAS_RESIDUAL = 2, // out(float) = resid(float) + acc + bias, in place allowed
+};
+
+// ---- launchers (all asynchronous on `s`) ---------------------------------------------------
+
+// h[m, :] = x[b, tok, :] * w_in + b_in + pos[p, :]
+void launch_embed(const float *x, const float *w_in, const float *b_in, const float *pos, float *h, int n_rows,
+                  int D, int W, RowMap map, hipStream_t s);
+
+// y = LayerNorm(x) * g + b over rows of width W (biased variance, eps 1e-5); OutT float or bf16
+template <typename OutT>
+void launch_layernorm(const float *x, const float *g, const float *b, OutT *y, int n_rows, int W, hipStream_t s);
+
+// float32 projection: C[M,N] = epi(A[M,K] * B[K,N] + bias)
+void launch_gemm_f32(const float *A, const float *B, const float *bias, const float *resid, float *C, int M, int N,
+                     int K, Epi epi, hipStream_t s);
+
+// bf16 MFMA projection: C[M,N] = epi(A[M,K] * Bt[N,K]^T + bias); Bt holds the weight transposed with
+// rows padded to `ldb` (>= K) and at least round_up(N, 128) rows (zero filled).  K % 64 == 0.
+// OutT bf16 (EPI_BIAS, EPI_BIAS_GELU) or float (EPI_BIAS, EPI_BIAS_RESIDUAL).
+template <typename OutT>
+void launch_gemm_bf16(const bf16 *A, const bf16 *Bt, const float *bias, const float *resid, OutT *C, int M, int N,
+                      int K, Epi epi, hipStream_t s);
+
+// Causal attention, one wave per (sample, head, query row); works for any shape and both types.
+// q rows: q + (sample*q_rows_per_sample + r) * q_stride; row r (processing position t0 + r) attends
+// keys 0..t0+r found at k + sample_index*kv_sample_stride + key*kv_stride (+ head*dh); same for v.
+// kv_index: nullptr => sample i uses cache slot i, else slot kv_index[i].
+template <typename QT, typename KVT>
+void launch_attention_rows(const QT *q, int64_t q_stride, const KVT *k, const KVT *v, int64_t kv_stride,
+                           int64_t kv_sample_stride, QT *o, int64_t o_stride, int n_samples, int q_rows_per_sample,
+                           int t0, int H, int dh, hipStream_t s);
+
+// Single-token step: writes this step's k, v (from the fused qkv row) into the cache at position t,
+// then attends keys 0..t.  qkv [B, 3W], cache [B, T, W] each for k and v, o [B, W].
+template <typename AT>
+void launch_decode_attention(const AT *qkv, AT *kcache, AT *vcache, AT *o, int B, int T, int t, int H, int dh,
+                             hipStream_t s);
+
+// Flash-style causal attention on bf16 qkv [n_samples*T, 3W] (head dim 64), o [n_samples*T, W].
+void launch_flash_attention_bf16(const bf16 *qkv, bf16 *o, int n_samples, int T, int H, hipStream_t s);
+
+// Jacobi epilogue.  p [n_rows, 2D] head output (row r of a sample parameterises position r+1).
+// For every listed sample that is still active: x <- z*exp(alpha)+mu in place, delta, pass count,
+// convergence flag.  Then the last workgroup rebuilds the active list.
+struct JacobiState {
+    float *delta;          // [B] last delta of each sample
+    int32_t *iters;        // [B] passes taken
+    int32_t *done;         // [B] 1 once converged or capped
+    int32_t *nonfinite;    // [1] set when a sample finishes with a non-finite delta
+    int32_t *active_in;    // [B] samples this pass ran on (n_listed entries)
+    int32_t *active_out;   // [B] compacted list of samples still running
+    int32_t *n_active_out; // [1]
+    uint32_t *ticket;      // [1] workgroup counter, zero before the launch, zero again after
+};
+void launch_jacobi_epilogue(const float *p, const float *z, float *x, JacobiState st, int n_listed, int T, int D,
+                            int reversed, float tau, int criterion, int cap, int drop_converged, hipStream_t s);
+
+// x^0 and state initialisation for a Jacobi block: x = 0 or z; iters = 0; done = 0; active = 0..B-1
+void launch_jacobi_init(const float *z, float *x, JacobiState st, int B, int T, int D, int init, hipStream_t s);
+
+// Sequential step epilogue: position t+1 of every sample from head row p[b, :]:
+// x[b, tok(t+1), :] = z[b, tok(t+1), :] * exp(alpha) + mu.  With t = -1 copies position 0 (x_1 = y_1).
+void launch_decode_epilogue(const float *p, const float *z, float *x, int B, int T, int D, int t, int reversed,
+                            hipStream_t s);
+
+// mu/alpha extraction for sjd_conditioner: shifted parameters in canonical order.
+void launch_split_params(const float *p, float *mu, float *alpha, int B, int T, int D, int reversed, hipStream_t s);
+
+// Weight preparation on the device: dst[n, k] (bf16, row length ldb, zero padded) = src[k, n] (float [K, N]).
+void launch_transpose_to_bf16(const float *src, bf16 *dst, int K, int N, int ldb, int n_rows_padded, hipStream_t s);
+
+}  // namespace sjd

@@ -1,0 +1,244 @@
+// Memory-bound kernels around the projections: token embedding, LayerNorm, the fused Jacobi
+// epilogue (affine update + difference reduction + convergence, Alg. 1), the sequential-step
+// epilogue (eq. 5 for one token), active-list compaction, and weight preparation.
+#include "common.h"
+
+namespace sjd {
+
+// ------------------------------------------------------------------------------------------------
+// Embedding: h[m, :] = x[b, tok, :] * w_in + b_in + pos[p, :]   (p = processing position of row m)
+// One workgroup per row; D is small (tens), W up to a few thousand.
+__global__ __launch_bounds__(256) void embed_kernel(const float *__restrict__ x, const float *__restrict__ w_in,
+                                                    const float *__restrict__ b_in, const float *__restrict__ pos,
+                                                    float *__restrict__ h, int D, int W, RowMap map) {
+    extern __shared__ float xs[];
+    const int m = blockIdx.x;
+    const int i = m / map.rows_per_sample;
+    const int p = map.t0 + m % map.rows_per_sample;
+    const int b = map.active ? map.active[i] : i;
+    const int tok = map.reversed ? map.T - 1 - p : p;
+    const float *xr = x + ((size_t)b * map.T + tok) * D;
+    for (int d = threadIdx.x; d < D; d += blockDim.x) xs[d] = xr[d];
+    __syncthreads();
+    for (int w = threadIdx.x; w < W; w += blockDim.x) {
+        float acc = b_in[w];
+        for (int d = 0; d < D; ++d) acc = fmaf(xs[d], w_in[(size_t)d * W + w], acc);
+        h[(size_t)m * W + w] = acc + pos[(size_t)p * W + w];
+    }
+}
+
+void launch_embed(const float *x, const float *w_in, const float *b_in, const float *pos, float *h, int n_rows, int D,
+                  int W, RowMap map, hipStream_t s) {
+    if (n_rows <= 0) return;
+    hipLaunchKernelGGL(embed_kernel, dim3(n_rows), dim3(256), D * sizeof(float), s, x, w_in, b_in, pos, h, D, W, map);
+}
+
+// ------------------------------------------------------------------------------------------------
+// LayerNorm: one wave per row, two-pass statistics in float32 (mean, then centred variance).
+template <typename OutT>
+__global__ __launch_bounds__(256) void layernorm_kernel(const float *__restrict__ x, const float *__restrict__ g,
+                                                        const float *__restrict__ b, OutT *__restrict__ y, int n_rows,
+                                                        int W) {
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (row >= n_rows) return;
+    const float *xr = x + (size_t)row * W;
+    float s = 0.f;
+    for (int i = lane; i < W; i += 64) s += xr[i];
+    const float mean = wave_sum(s) / (float)W;
+    float v = 0.f;
+    for (int i = lane; i < W; i += 64) { float d = xr[i] - mean; v = fmaf(d, d, v); }
+    const float rstd = 1.0f / sqrtf(wave_sum(v) / (float)W + 1e-5f);
+    OutT *yr = y + (size_t)row * W;
+    for (int i = lane; i < W; i += 64) yr[i] = from_f32<OutT>((xr[i] - mean) * rstd * g[i] + b[i]);
+}
+
+template <typename OutT>
+void launch_layernorm(const float *x, const float *g, const float *b, OutT *y, int n_rows, int W, hipStream_t s) {
+    if (n_rows <= 0) return;
+    hipLaunchKernelGGL(layernorm_kernel<OutT>, dim3((n_rows + 3) / 4), dim3(256), 0, s, x, g, b, y, n_rows, W);
+}
+template void launch_layernorm<float>(const float *, const float *, const float *, float *, int, int, hipStream_t);
+template void launch_layernorm<bf16>(const float *, const float *, const float *, bf16 *, int, int, hipStream_t);
+
+// ------------------------------------------------------------------------------------------------
+// Jacobi epilogue (Alg. 1, the update line and the stopping test; F of Def. A.1).
+// One workgroup per listed sample.  The difference norm is reduced in a fixed order (lane
+// partials -> wave shuffles -> waves in index order), so a sample's delta does not depend on
+// which other samples are in flight.
+
+__device__ __forceinline__ float nan_max(float a, float d) { return (d > a || d != d) ? d : a; }
+
+__global__ __launch_bounds__(256) void jacobi_epilogue_kernel(const float *__restrict__ p, const float *__restrict__ z,
+                                                              float *__restrict__ x, JacobiState st, int T, int D,
+                                                              int reversed, float tau, int criterion, int cap) {
+    __shared__ float part[4];
+    const int i = blockIdx.x;
+    const int b = st.active_in[i];
+    if (st.done[b]) return;  // only reachable when converged samples are kept in the batch
+    const int n = T * D;
+    const float *pr = p + (size_t)i * T * 2 * D;
+    float acc = 0.f;
+    for (int e = threadIdx.x; e < n; e += 256) {
+        const int l = e / D, d = e - l * D;
+        const int tok = reversed ? T - 1 - l : l;
+        const size_t idx = ((size_t)b * T + tok) * D + d;
+        float xn = z[idx];
+        if (l > 0) {
+            const float mu = pr[(size_t)(l - 1) * 2 * D + d];
+            const float al = pr[(size_t)(l - 1) * 2 * D + D + d];
+            xn = fmaf(xn, expf(al), mu);
+        }
+        const float diff = fabsf(xn - x[idx]);
+        x[idx] = xn;
+        acc = criterion == 1 ? nan_max(acc, diff) : acc + diff;
+    }
+    if (criterion == 1) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) acc = nan_max(acc, __shfl_xor(acc, o, 64));
+    } else {
+        acc = wave_sum(acc);
+    }
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float delta;
+        if (criterion == 1) delta = nan_max(nan_max(nan_max(part[0], part[1]), part[2]), part[3]);
+        else delta = (((part[0] + part[1]) + part[2]) + part[3]) / (float)n;
+        const int it = st.iters[b] + 1;
+        st.iters[b] = it;
+        st.delta[b] = delta;
+        if (delta < tau || it >= cap) {
+            st.done[b] = 1;
+            if (!(fabsf(delta) <= 3.0e38f)) *st.nonfinite = 1;
+        }
+    }
+}
+
+// Rebuilds the list of samples that still iterate (in increasing order) and counts them.
+// With keep_all the list is left complete and only the count of unfinished samples is produced.
+__global__ __launch_bounds__(256) void compact_active_kernel(JacobiState st, int n_listed, int keep_all) {
+    __shared__ int wave_keep[4], wave_live[4];
+    __shared__ int base_keep, base_live;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    if (threadIdx.x == 0) { base_keep = 0; base_live = 0; }
+    __syncthreads();
+    for (int start = 0; start < n_listed; start += 256) {
+        const int i = start + threadIdx.x;
+        int b = -1, live = 0;
+        if (i < n_listed) { b = st.active_in[i]; live = st.done[b] ? 0 : 1; }
+        const int keep = (i < n_listed) && (keep_all || live);
+        const unsigned long long mk = __ballot(keep), ml = __ballot(live);
+        const int before = __popcll(mk & ((1ull << lane) - 1ull));
+        if (lane == 0) { wave_keep[wv] = __popcll(mk); wave_live[wv] = __popcll(ml); }
+        __syncthreads();
+        int off = base_keep;
+        for (int w = 0; w < wv; ++w) off += wave_keep[w];
+        if (keep) st.active_out[off + before] = b;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            base_keep += wave_keep[0] + wave_keep[1] + wave_keep[2] + wave_keep[3];
+            base_live += wave_live[0] + wave_live[1] + wave_live[2] + wave_live[3];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *st.n_active_out = base_live;
+}
+
+void launch_jacobi_epilogue(const float *p, const float *z, float *x, JacobiState st, int n_listed, int T, int D,
+                            int reversed, float tau, int criterion, int cap, int drop_converged, hipStream_t s) {
+    if (n_listed <= 0) return;
+    hipLaunchKernelGGL(jacobi_epilogue_kernel, dim3(n_listed), dim3(256), 0, s, p, z, x, st, T, D, reversed, tau,
+                       criterion, cap);
+    hipLaunchKernelGGL(compact_active_kernel, dim3(1), dim3(256), 0, s, st, n_listed, drop_converged ? 0 : 1);
+}
+
+__global__ __launch_bounds__(256) void jacobi_init_kernel(const float *__restrict__ z, float *__restrict__ x,
+                                                          JacobiState st, int B, size_t n_per_sample, int init) {
+    const size_t n = (size_t)B * n_per_sample;
+    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < n; e += (size_t)gridDim.x * 256)
+        x[e] = init == 1 ? z[e] : 0.f;
+    if (blockIdx.x == 0) {
+        for (int b = threadIdx.x; b < B; b += 256) {
+            st.iters[b] = 0; st.done[b] = 0; st.delta[b] = 0.f; st.active_in[b] = b; st.active_out[b] = b;
+        }
+        if (threadIdx.x == 0) { *st.n_active_out = B; *st.nonfinite = 0; }
+    }
+}
+
+void launch_jacobi_init(const float *z, float *x, JacobiState st, int B, int T, int D, int init, hipStream_t s) {
+    const size_t n = (size_t)B * T * D;
+    int grid = (int)((n + 255) / 256);
+    if (grid > 2048) grid = 2048;
+    if (grid < 1) grid = 1;
+    hipLaunchKernelGGL(jacobi_init_kernel, dim3(grid), dim3(256), 0, s, z, x, st, B, (size_t)T * D, init);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Sequential step epilogue (eq. 5, one token of every sample).
+__global__ void decode_epilogue_kernel(const float *__restrict__ p, const float *__restrict__ z, float *__restrict__ x,
+                                       int T, int D, int t, int reversed) {
+    const int b = blockIdx.x;
+    const int l = t + 1;
+    const int tok = reversed ? T - 1 - l : l;
+    for (int d = threadIdx.x; d < D; d += blockDim.x) {
+        const size_t idx = ((size_t)b * T + tok) * D + d;
+        float xn = z[idx];
+        if (l > 0) xn = fmaf(xn, expf(p[(size_t)b * 2 * D + D + d]), p[(size_t)b * 2 * D + d]);
+        x[idx] = xn;
+    }
+}
+
+void launch_decode_epilogue(const float *p, const float *z, float *x, int B, int T, int D, int t, int reversed,
+                            hipStream_t s) {
+    if (B <= 0) return;
+    hipLaunchKernelGGL(decode_epilogue_kernel, dim3(B), dim3(64), 0, s, p, z, x, T, D, t, reversed);
+}
+
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void split_params_kernel(const float *__restrict__ p, float *__restrict__ mu,
+                                                           float *__restrict__ alpha, int T, int D, int reversed) {
+    const int b = blockIdx.x;
+    for (int e = threadIdx.x; e < T * D; e += 256) {
+        const int l = e / D, d = e - l * D;
+        const int tok = reversed ? T - 1 - l : l;
+        const size_t idx = ((size_t)b * T + tok) * D + d;
+        float m = 0.f, a = 0.f;
+        if (l > 0) {
+            m = p[((size_t)b * T + l - 1) * 2 * D + d];
+            a = p[((size_t)b * T + l - 1) * 2 * D + D + d];
+        }
+        mu[idx] = m;
+        alpha[idx] = a;
+    }
+}
+
+void launch_split_params(const float *p, float *mu, float *alpha, int B, int T, int D, int reversed, hipStream_t s) {
+    if (B <= 0) return;
+    hipLaunchKernelGGL(split_params_kernel, dim3(B), dim3(256), 0, s, p, mu, alpha, T, D, reversed);
+}
+
+// ------------------------------------------------------------------------------------------------
+// dst[n, k] = bf16(src[k, n]) for n < N, k < K; zero elsewhere (rows up to n_rows_padded, row length ldb)
+__global__ __launch_bounds__(256) void transpose_to_bf16_kernel(const float *__restrict__ src, bf16 *__restrict__ dst,
+                                                                int K, int N, int ldb, int n_rows_padded) {
+    __shared__ float tile[32][33];
+    const int k0 = blockIdx.x * 32, n0 = blockIdx.y * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+    for (int r = ty; r < 32; r += 8) {
+        const int k = k0 + r, n = n0 + tx;
+        tile[r][tx] = (k < K && n < N) ? src[(size_t)k * N + n] : 0.f;
+    }
+    __syncthreads();
+    for (int r = ty; r < 32; r += 8) {
+        const int n = n0 + r, k = k0 + tx;
+        if (n < n_rows_padded && k < ldb) dst[(size_t)n * ldb + k] = (bf16)tile[tx][r];
+    }
+}
+
+void launch_transpose_to_bf16(const float *src, bf16 *dst, int K, int N, int ldb, int n_rows_padded, hipStream_t s) {
+    dim3 grid((ldb + 31) / 32, (n_rows_padded + 31) / 32);
+    hipLaunchKernelGGL(transpose_to_bf16_kernel, grid, dim3(256), 0, s, src, dst, K, N, ldb, n_rows_padded);
+}
+
+}  // namespace sjd

@@ -1,0 +1,568 @@
+// Host side of the library: the handle, weight loading, and the entry points declared in sjd.h.
+// Every arithmetic step runs in the HIP kernels of this directory; the host only sequences
+// launches and reads one integer per Jacobi pass (the number of samples still iterating).
+#include "../../include/sjd.h"
+
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "common.h"
+
+using namespace sjd;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                                  \
+    do {                                                                                               \
+        hipError_t e_ = (expr);                                                                        \
+        if (e_ != hipSuccess) return fail(SJD_EHIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), \
+                                          __FILE__, __LINE__);                                         \
+    } while (0)
+
+struct LayerW {
+    const float *ln1_g, *ln1_b, *b_qkv, *b_o, *ln2_g, *ln2_b, *b_fc1, *b_fc2;
+    const float *w_qkv, *w_o, *w_fc1, *w_fc2;      // float32 [in, out] (views into the device blob)
+    bf16 *t_qkv, *t_o, *t_fc1, *t_fc2;             // bf16 transposed [out (padded), in]
+};
+struct BlockW {
+    const float *w_in, *b_in, *pos, *lnf_g, *lnf_b, *w_head, *b_head;
+    bf16 *t_head;
+    std::vector<LayerW> layer;
+};
+
+struct ProfSpan { hipEvent_t a, b; int fam; };
+
+}  // namespace
+
+struct sjd_flow {
+    sjd_config cfg;
+    int device = 0;
+    bool loaded = false;
+    size_t bytes = 0;
+    std::vector<void *> allocs;
+    float *blob = nullptr;       // whole float32 blob on the device
+    bf16 *arena = nullptr;       // transposed bf16 matrices
+    std::vector<BlockW> block;
+    // workspaces (element type depends on dtype: float or bf16 for a, qkv, o, f and the cache)
+    float *h = nullptr, *p = nullptr;
+    void *a = nullptr, *qkv = nullptr, *o = nullptr, *f = nullptr;
+    void *kcache = nullptr, *vcache = nullptr;  // [N][B][T][W]
+    float *pp[2] = {nullptr, nullptr};          // block outputs inside sjd_sample
+    JacobiState st{};
+    int32_t *active[2] = {nullptr, nullptr};
+    int32_t *host_pin = nullptr;                // pinned: [0] n_active, [1] nonfinite, [2..] iters[B]
+    hipEvent_t ev[SJD_MAX_BLOCKS + 1] = {};
+    // profiling
+    uint32_t prof_mask = 0;
+    std::vector<ProfSpan> spans;
+    std::vector<hipEvent_t> free_events;
+    sjd_profile prof{};
+};
+
+namespace {
+
+size_t act_bytes(const sjd_flow *f) { return f->cfg.dtype == SJD_DTYPE_BF16 ? 2 : 4; }
+
+int dev_alloc(sjd_flow *f, void **out, size_t nbytes) {
+    if (nbytes == 0) nbytes = 256;
+    hipError_t e = hipMalloc(out, nbytes);
+    if (e != hipSuccess) return fail(SJD_ENOMEM, "hipMalloc of %zu bytes failed: %s", nbytes, hipGetErrorString(e));
+    f->allocs.push_back(*out);
+    f->bytes += nbytes;
+    return SJD_OK;
+}
+
+size_t round_up(size_t v, size_t m) { return (v + m - 1) / m * m; }
+
+size_t block_floats(const sjd_config &c) {
+    size_t D = c.token_dim, W = c.width, T = c.seq_len, R = c.mlp_ratio, N = c.n_layers;
+    size_t per_layer = 2 * W + W * 3 * W + 3 * W + W * W + W + 2 * W + W * R * W + R * W + R * W * W + W;
+    return D * W + W + T * W + N * per_layer + 2 * W + W * 2 * D + 2 * D;
+}
+
+constexpr size_t kNPad = 256;  // transposed weights are padded to this many rows per matrix
+
+size_t arena_elems_per_block(const sjd_config &c) {
+    size_t W = c.width, R = c.mlp_ratio, D = c.token_dim;
+    size_t per_layer = round_up(3 * W, kNPad) * W + round_up(W, kNPad) * W + round_up(R * W, kNPad) * W +
+                       round_up(W, kNPad) * R * W;
+    return c.n_layers * per_layer + round_up(2 * D, kNPad) * W;
+}
+
+// ---- profiling helpers ---------------------------------------------------------------------------
+struct ProfScope {
+    sjd_flow *f; int fam; hipStream_t s; bool on; hipEvent_t a{}, b{};
+    ProfScope(sjd_flow *f_, int fam_, double flops, double bytes, hipStream_t s_) : f(f_), fam(fam_), s(s_) {
+        on = (f->prof_mask >> fam) & 1u;
+        if (!on) return;
+        auto get = [&]() {
+            hipEvent_t e;
+            if (!f->free_events.empty()) { e = f->free_events.back(); f->free_events.pop_back(); }
+            else if (hipEventCreate(&e) != hipSuccess) { e = nullptr; }
+            return e;
+        };
+        a = get(); b = get();
+        if (!a || !b) { on = false; return; }
+        f->prof.flops[fam] += flops;
+        f->prof.bytes[fam] += bytes;
+        f->prof.launches[fam] += 1;
+        (void)hipEventRecord(a, s);
+    }
+    ~ProfScope() {
+        if (!on) return;
+        (void)hipEventRecord(b, s);
+        f->spans.push_back({a, b, fam});
+    }
+};
+
+int drain_profile(sjd_flow *f) {
+    for (auto &sp : f->spans) {
+        HIP_TRY(hipEventSynchronize(sp.b));
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, sp.a, sp.b));
+        f->prof.ms[sp.fam] += ms;
+        f->free_events.push_back(sp.a);
+        f->free_events.push_back(sp.b);
+    }
+    f->spans.clear();
+    return SJD_OK;
+}
+
+// ---- one projection, in the flow's precision ----------------------------------------------------
+// in: A [M, K]; out: C [M, N]; residual variant accumulates into the float32 stream h in place.
+void project(sjd_flow *f, int fam, const void *A, const float *w32, const bf16 *wt, const float *bias, void *C, int M,
+             int N, int K, Epi epi, bool out_f32, hipStream_t s) {
+    const bool bf = f->cfg.dtype == SJD_DTYPE_BF16;
+    const double in_b = bf ? 2.0 : 4.0, out_b = (bf && !out_f32) ? 2.0 : 4.0;
+    double bytes = (double)M * K * in_b + (double)K * N * in_b + (double)M * N * out_b + (double)N * 4;
+    if (epi == EPI_BIAS_RESIDUAL) bytes += (double)M * N * 4;
+    ProfScope ps(f, fam, 2.0 * M * (double)N * K, bytes, s);
+    if (!bf) {
+        launch_gemm_f32((const float *)A, w32, bias, epi == EPI_BIAS_RESIDUAL ? (const float *)C : nullptr, (float *)C,
+                        M, N, K, epi, s);
+    } else if (out_f32) {
+        launch_gemm_bf16<float>((const bf16 *)A, wt, bias, epi == EPI_BIAS_RESIDUAL ? (const float *)C : nullptr,
+                                (float *)C, M, N, K, epi, s);
+    } else {
+        launch_gemm_bf16<bf16>((const bf16 *)A, wt, bias, nullptr, (bf16 *)C, M, N, K, epi, s);
+    }
+}
+
+void layernorm(sjd_flow *f, const float *x, const float *g, const float *b, void *y, int rows, hipStream_t s) {
+    const int W = f->cfg.width;
+    ProfScope ps(f, SJD_PROF_OTHER, 0.0, (double)rows * W * (4.0 + act_bytes(f)), s);
+    if (f->cfg.dtype == SJD_DTYPE_BF16) launch_layernorm<bf16>(x, g, b, (bf16 *)y, rows, W, s);
+    else launch_layernorm<float>(x, g, b, (float *)y, rows, W, s);
+}
+
+// Whole-sequence conditioner pass on `n` samples listed in `active` (device, nullable = identity).
+// Leaves the head output in f->p: [n*T, 2D], row r of a sample = parameters of position r+1.
+void conditioner_pass(sjd_flow *f, int j, const float *x, int n, const int32_t *active, hipStream_t s) {
+    const sjd_config &c = f->cfg;
+    const int T = c.seq_len, W = c.width, D = c.token_dim, H = c.n_heads, RW = c.mlp_ratio * c.width;
+    const int M = n * T;
+    const int rev = (c.reverse_mask >> j) & 1;
+    const bool bf = c.dtype == SJD_DTYPE_BF16;
+    const BlockW &bw = f->block[j];
+    {
+        ProfScope ps(f, SJD_PROF_OTHER, 2.0 * M * (double)D * W, (double)M * W * 4, s);
+        launch_embed(x, bw.w_in, bw.b_in, bw.pos, f->h, M, D, W, RowMap{active, T, 0, T, rev}, s);
+    }
+    for (int l = 0; l < c.n_layers; ++l) {
+        const LayerW &lw = bw.layer[l];
+        layernorm(f, f->h, lw.ln1_g, lw.ln1_b, f->a, M, s);
+        project(f, SJD_PROF_GEMM, f->a, lw.w_qkv, lw.t_qkv, lw.b_qkv, f->qkv, M, 3 * W, W, EPI_BIAS, false, s);
+        {
+            const double ab = act_bytes(f);
+            ProfScope ps(f, SJD_PROF_ATTENTION, 2.0 * n * (double)T * (T + 1) * W, (double)M * 4 * W * ab, s);
+            if (bf && W / H == 64) {
+                launch_flash_attention_bf16((const bf16 *)f->qkv, (bf16 *)f->o, n, T, H, s);
+            } else if (bf) {
+                const bf16 *q = (const bf16 *)f->qkv;
+                launch_attention_rows<bf16, bf16>(q, 3 * W, q + W, q + 2 * W, 3 * W, (int64_t)T * 3 * W, (bf16 *)f->o, W,
+                                                  n, T, 0, H, W / H, s);
+            } else {
+                const float *q = (const float *)f->qkv;
+                launch_attention_rows<float, float>(q, 3 * W, q + W, q + 2 * W, 3 * W, (int64_t)T * 3 * W,
+                                                    (float *)f->o, W, n, T, 0, H, W / H, s);
+            }
+        }
+        project(f, SJD_PROF_GEMM, f->o, lw.w_o, lw.t_o, lw.b_o, f->h, M, W, W, EPI_BIAS_RESIDUAL, true, s);
+        layernorm(f, f->h, lw.ln2_g, lw.ln2_b, f->a, M, s);
+        project(f, SJD_PROF_GEMM, f->a, lw.w_fc1, lw.t_fc1, lw.b_fc1, f->f, M, RW, W, EPI_BIAS_GELU, false, s);
+        project(f, SJD_PROF_GEMM, f->f, lw.w_fc2, lw.t_fc2, lw.b_fc2, f->h, M, W, RW, EPI_BIAS_RESIDUAL, true, s);
+    }
+    layernorm(f, f->h, bw.lnf_g, bw.lnf_b, f->a, M, s);
+    project(f, SJD_PROF_GEMM, f->a, bw.w_head, bw.t_head, bw.b_head, f->p, M, 2 * D, W, EPI_BIAS, true, s);
+}
+
+// One single-token step of the sequential inverse: position t of every sample goes through all
+// layers against the key/value cache; the head output parameterises position t+1.
+void decode_step(sjd_flow *f, int j, const float *z, float *x, int B, int t, hipStream_t s) {
+    const sjd_config &c = f->cfg;
+    const int T = c.seq_len, W = c.width, D = c.token_dim, H = c.n_heads, RW = c.mlp_ratio * c.width;
+    const int rev = (c.reverse_mask >> j) & 1;
+    const bool bf = c.dtype == SJD_DTYPE_BF16;
+    const BlockW &bw = f->block[j];
+    const size_t ab = act_bytes(f);
+    {
+        ProfScope ps(f, SJD_PROF_OTHER, 2.0 * B * (double)D * W, (double)B * W * 4, s);
+        launch_embed(x, bw.w_in, bw.b_in, bw.pos, f->h, B, D, W, RowMap{nullptr, 1, t, T, rev}, s);
+    }
+    for (int l = 0; l < c.n_layers; ++l) {
+        const LayerW &lw = bw.layer[l];
+        layernorm(f, f->h, lw.ln1_g, lw.ln1_b, f->a, B, s);
+        project(f, SJD_PROF_DECODE_GEMM, f->a, lw.w_qkv, lw.t_qkv, lw.b_qkv, f->qkv, B, 3 * W, W, EPI_BIAS, false, s);
+        {
+            const size_t layer_off = (size_t)l * c.max_batch * T * W * ab;
+            ProfScope ps(f, SJD_PROF_DECODE_ATTN, 4.0 * B * (double)(t + 1) * W,
+                         (double)B * (2.0 * (t + 1) * W + 4.0 * W) * ab, s);
+            if (bf)
+                launch_decode_attention<bf16>((const bf16 *)f->qkv, (bf16 *)((char *)f->kcache + layer_off),
+                                              (bf16 *)((char *)f->vcache + layer_off), (bf16 *)f->o, B, T, t, H, W / H, s);
+            else
+                launch_decode_attention<float>((const float *)f->qkv, (float *)((char *)f->kcache + layer_off),
+                                               (float *)((char *)f->vcache + layer_off), (float *)f->o, B, T, t, H,
+                                               W / H, s);
+        }
+        project(f, SJD_PROF_DECODE_GEMM, f->o, lw.w_o, lw.t_o, lw.b_o, f->h, B, W, W, EPI_BIAS_RESIDUAL, true, s);
+        layernorm(f, f->h, lw.ln2_g, lw.ln2_b, f->a, B, s);
+        project(f, SJD_PROF_DECODE_GEMM, f->a, lw.w_fc1, lw.t_fc1, lw.b_fc1, f->f, B, RW, W, EPI_BIAS_GELU, false, s);
+        project(f, SJD_PROF_DECODE_GEMM, f->f, lw.w_fc2, lw.t_fc2, lw.b_fc2, f->h, B, W, RW, EPI_BIAS_RESIDUAL, true, s);
+    }
+    layernorm(f, f->h, bw.lnf_g, bw.lnf_b, f->a, B, s);
+    project(f, SJD_PROF_DECODE_GEMM, f->a, bw.w_head, bw.t_head, bw.b_head, f->p, B, 2 * D, W, EPI_BIAS, true, s);
+    {
+        ProfScope ps(f, SJD_PROF_EPILOGUE, 0.0, (double)B * D * 16.0, s);
+        launch_decode_epilogue(f->p, z, x, B, T, D, t, rev, s);
+    }
+}
+
+int check_call(const sjd_flow *f, int block, const void *z, const void *x, int batch) {
+    if (!f) return fail(SJD_EINVAL, "null flow handle");
+    if (!f->loaded) return fail(SJD_ESTATE, "weights have not been loaded");
+    if (!z || !x) return fail(SJD_EINVAL, "null device pointer");
+    if (batch < 0 || batch > f->cfg.max_batch)
+        return fail(SJD_EINVAL, "batch %d outside 0..max_batch=%d", batch, f->cfg.max_batch);
+    if (block < 0 || block >= f->cfg.n_blocks) return fail(SJD_EINVAL, "block %d outside 0..%d", block, f->cfg.n_blocks - 1);
+    const size_t n = (size_t)batch * f->cfg.seq_len * f->cfg.token_dim * sizeof(float);
+    const char *a = (const char *)z, *b = (const char *)x;
+    if (n && a < b + n && b < a + n) return fail(SJD_EINVAL, "input and output buffers overlap");
+    return SJD_OK;
+}
+
+int check_opts(const sjd_jacobi_opts *o) {
+    if (!o) return fail(SJD_EINVAL, "null options");
+    if (o->tau != o->tau) return fail(SJD_EINVAL, "tau is NaN");
+    if (o->criterion != 0 && o->criterion != 1) return fail(SJD_EINVAL, "criterion must be 0 or 1");
+    if (o->init != 0 && o->init != 1) return fail(SJD_EINVAL, "init must be 0 (zeros) or 1 (block input)");
+    if (o->max_iters < 0) return fail(SJD_EINVAL, "max_iters is negative");
+    return SJD_OK;
+}
+
+// Alg. 1 for one block.  iters_pin (pinned host, [batch]) receives per-sample pass counts.
+int run_jacobi(sjd_flow *f, int j, const float *z, float *x, int batch, const sjd_jacobi_opts *opts, int *passes_out,
+               bool *nonfinite_out, hipStream_t s) {
+    const sjd_config &c = f->cfg;
+    const int T = c.seq_len, D = c.token_dim;
+    const int rev = (c.reverse_mask >> j) & 1;
+    const int cap = (opts->max_iters > 0 && opts->max_iters < T) ? opts->max_iters : T;
+    *passes_out = 0;
+    *nonfinite_out = false;
+    if (batch == 0) return SJD_OK;
+    JacobiState st = f->st;
+    st.active_in = f->active[0];
+    st.active_out = f->active[1];
+    launch_jacobi_init(z, x, st, batch, T, D, opts->init, s);
+    int n_live = batch, n_listed = batch, passes = 0;
+    while (n_live > 0 && passes < cap) {
+        conditioner_pass(f, j, x, n_listed, st.active_in, s);
+        {
+            ProfScope ps(f, SJD_PROF_EPILOGUE, 0.0, (double)n_listed * T * D * 24.0, s);
+            launch_jacobi_epilogue(f->p, z, x, st, n_listed, T, D, rev, opts->tau, opts->criterion, cap,
+                                   opts->drop_converged, s);
+        }
+        HIP_TRY(hipMemcpyAsync(f->host_pin, st.n_active_out, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        HIP_TRY(hipGetLastError());
+        n_live = f->host_pin[0];
+        if (n_live < 0 || n_live > batch) return fail(SJD_EHIP, "active-sample count %d is out of range", n_live);
+        if (opts->drop_converged) n_listed = n_live;
+        int32_t *t = st.active_in; st.active_in = st.active_out; st.active_out = t;
+        ++passes;
+    }
+    HIP_TRY(hipMemcpyAsync(f->host_pin + 1, st.nonfinite, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipMemcpyAsync(f->host_pin + 2, st.iters, sizeof(int32_t) * batch, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    *passes_out = passes;
+    *nonfinite_out = f->host_pin[1] != 0;
+    return SJD_OK;
+}
+
+int run_sequential(sjd_flow *f, int j, const float *z, float *x, int batch, hipStream_t s) {
+    const int T = f->cfg.seq_len, D = f->cfg.token_dim;
+    const int rev = (f->cfg.reverse_mask >> j) & 1;
+    if (batch == 0) return SJD_OK;
+    launch_decode_epilogue(f->p, z, x, batch, T, D, -1, rev, s);  // x_1 = y_1
+    for (int t = 0; t + 1 < T; ++t) decode_step(f, j, z, x, batch, t, s);
+    HIP_TRY(hipGetLastError());
+    return SJD_OK;
+}
+
+}  // namespace
+
+// ================================================================================================
+extern "C" {
+
+const char *sjd_last_error(void) { return g_err; }
+
+int sjd_flow_create(const sjd_config *cfg, sjd_flow **out) {
+    if (!cfg || !out) return fail(SJD_EINVAL, "null argument");
+    *out = nullptr;
+    const sjd_config &c = *cfg;
+    if (c.n_blocks < 1 || c.n_blocks > SJD_MAX_BLOCKS) return fail(SJD_EINVAL, "n_blocks must be 1..%d", SJD_MAX_BLOCKS);
+    if (c.n_layers < 1 || c.width < 1 || c.n_heads < 1 || c.mlp_ratio < 1 || c.seq_len < 1 || c.token_dim < 1 ||
+        c.max_batch < 1)
+        return fail(SJD_EINVAL, "all sizes must be positive");
+    if (c.width % c.n_heads) return fail(SJD_EINVAL, "width %d is not a multiple of n_heads %d", c.width, c.n_heads);
+    if (c.dtype != SJD_DTYPE_F32 && c.dtype != SJD_DTYPE_BF16) return fail(SJD_EINVAL, "unknown dtype %d", c.dtype);
+    if (c.dtype == SJD_DTYPE_BF16 && c.width % 64) return fail(SJD_EINVAL, "bf16 mode needs width %% 64 == 0");
+    if (c.seq_len > 4096) return fail(SJD_EINVAL, "seq_len above 4096 is not supported");
+    if (c.token_dim > 1024) return fail(SJD_EINVAL, "token_dim above 1024 is not supported");
+    if ((double)c.max_batch * c.seq_len > 1.0e9) return fail(SJD_EINVAL, "max_batch * seq_len is too large");
+
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) return fail(SJD_EHIP, "no HIP device is available");
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    hipDeviceProp_t prop;
+    HIP_TRY(hipGetDeviceProperties(&prop, dev));
+    if (strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+        return fail(SJD_EHIP, "device %d is %s; this library is built for gfx950 only", dev, prop.gcnArchName);
+
+    sjd_flow *f = new (std::nothrow) sjd_flow();
+    if (!f) return fail(SJD_ENOMEM, "host allocation failed");
+    f->cfg = c;
+    f->device = dev;
+    const size_t T = c.seq_len, W = c.width, D = c.token_dim, R = c.mlp_ratio, B = c.max_batch, N = c.n_layers;
+    const size_t M = B * T, ab = act_bytes(f);
+    int rc = SJD_OK;
+    auto A = [&](void **p, size_t n) { if (rc == SJD_OK) rc = dev_alloc(f, p, n); };
+    A((void **)&f->blob, (size_t)c.n_blocks * block_floats(c) * sizeof(float));
+    if (c.dtype == SJD_DTYPE_BF16) A((void **)&f->arena, (size_t)c.n_blocks * arena_elems_per_block(c) * sizeof(bf16));
+    A((void **)&f->h, M * W * 4);
+    A((void **)&f->p, M * 2 * D * 4);
+    A(&f->a, M * W * ab);
+    A(&f->qkv, M * 3 * W * ab);
+    A(&f->o, M * W * ab);
+    A(&f->f, M * R * W * ab);
+    A(&f->kcache, N * B * T * W * ab);
+    A(&f->vcache, N * B * T * W * ab);
+    A((void **)&f->pp[0], M * D * 4);
+    A((void **)&f->pp[1], M * D * 4);
+    A((void **)&f->st.delta, B * 4);
+    A((void **)&f->st.iters, B * 4);
+    A((void **)&f->st.done, B * 4);
+    A((void **)&f->st.nonfinite, 4);
+    A((void **)&f->st.n_active_out, 4);
+    A((void **)&f->active[0], B * 4);
+    A((void **)&f->active[1], B * 4);
+    f->st.ticket = nullptr;
+    if (rc == SJD_OK && hipHostMalloc((void **)&f->host_pin, (B + 2) * sizeof(int32_t)) != hipSuccess)
+        rc = fail(SJD_ENOMEM, "pinned host allocation failed");
+    for (int i = 0; rc == SJD_OK && i <= c.n_blocks; ++i)
+        if (hipEventCreate(&f->ev[i]) != hipSuccess) rc = fail(SJD_EHIP, "hipEventCreate failed");
+    if (rc != SJD_OK) { sjd_flow_destroy(f); return rc; }
+    *out = f;
+    return SJD_OK;
+}
+
+void sjd_flow_destroy(sjd_flow *f) {
+    if (!f) return;
+    (void)hipDeviceSynchronize();
+    for (void *p : f->allocs) (void)hipFree(p);
+    if (f->host_pin) (void)hipHostFree(f->host_pin);
+    for (auto &e : f->ev) if (e) (void)hipEventDestroy(e);
+    for (auto &sp : f->spans) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
+    for (auto &e : f->free_events) (void)hipEventDestroy(e);
+    delete f;
+}
+
+size_t sjd_flow_device_bytes(const sjd_flow *f) { return f ? f->bytes : 0; }
+
+int sjd_flow_load_weights(sjd_flow *f, const void *host_blob, size_t nbytes) {
+    if (!f || !host_blob) return fail(SJD_EINVAL, "null argument");
+    const sjd_config &c = f->cfg;
+    const size_t bf = block_floats(c);
+    const size_t want = (size_t)c.n_blocks * bf * sizeof(float);
+    if (nbytes != want) return fail(SJD_EINVAL, "weight blob has %zu bytes, the configuration implies %zu", nbytes, want);
+    HIP_TRY(hipMemcpy(f->blob, host_blob, nbytes, hipMemcpyHostToDevice));
+    const size_t D = c.token_dim, W = c.width, T = c.seq_len, R = c.mlp_ratio;
+    const bool b16 = c.dtype == SJD_DTYPE_BF16;
+    f->block.assign(c.n_blocks, BlockW());
+    bf16 *ar = f->arena;
+    auto prep = [&](const float *src, size_t K, size_t N) -> bf16 * {  // [K, N] float -> [N padded, K] bf16
+        if (!b16) return nullptr;
+        bf16 *dst = ar;
+        const size_t rows = round_up(N, kNPad);
+        launch_transpose_to_bf16(src, dst, (int)K, (int)N, (int)K, (int)rows, 0);
+        ar += rows * K;
+        return dst;
+    };
+    for (int j = 0; j < c.n_blocks; ++j) {
+        const float *p = f->blob + (size_t)j * bf;
+        BlockW &bw = f->block[j];
+        bw.w_in = p; p += D * W;
+        bw.b_in = p; p += W;
+        bw.pos = p; p += T * W;
+        bw.layer.resize(c.n_layers);
+        for (int l = 0; l < c.n_layers; ++l) {
+            LayerW &lw = bw.layer[l];
+            lw.ln1_g = p; p += W;
+            lw.ln1_b = p; p += W;
+            lw.w_qkv = p; p += W * 3 * W;
+            lw.b_qkv = p; p += 3 * W;
+            lw.w_o = p; p += W * W;
+            lw.b_o = p; p += W;
+            lw.ln2_g = p; p += W;
+            lw.ln2_b = p; p += W;
+            lw.w_fc1 = p; p += W * R * W;
+            lw.b_fc1 = p; p += R * W;
+            lw.w_fc2 = p; p += R * W * W;
+            lw.b_fc2 = p; p += W;
+            lw.t_qkv = prep(lw.w_qkv, W, 3 * W);
+            lw.t_o = prep(lw.w_o, W, W);
+            lw.t_fc1 = prep(lw.w_fc1, W, R * W);
+            lw.t_fc2 = prep(lw.w_fc2, R * W, W);
+        }
+        bw.lnf_g = p; p += W;
+        bw.lnf_b = p; p += W;
+        bw.w_head = p; p += W * 2 * D;
+        bw.b_head = p;
+        bw.t_head = prep(bw.w_head, W, 2 * D);
+    }
+    HIP_TRY(hipDeviceSynchronize());
+    HIP_TRY(hipGetLastError());
+    f->loaded = true;
+    return SJD_OK;
+}
+
+int sjd_conditioner(sjd_flow *f, int block, const float *x_dev, float *mu_dev, float *alpha_dev, int batch,
+                    void *hip_stream) {
+    int rc = check_call(f, block, x_dev, mu_dev, batch);
+    if (rc) return rc;
+    if (!alpha_dev) return fail(SJD_EINVAL, "null device pointer");
+    hipStream_t s = (hipStream_t)hip_stream;
+    HIP_TRY(hipSetDevice(f->device));
+    conditioner_pass(f, block, x_dev, batch, nullptr, s);
+    launch_split_params(f->p, mu_dev, alpha_dev, batch, f->cfg.seq_len, f->cfg.token_dim,
+                        (f->cfg.reverse_mask >> block) & 1, s);
+    HIP_TRY(hipStreamSynchronize(s));
+    HIP_TRY(hipGetLastError());
+    return SJD_OK;
+}
+
+int sjd_jacobi_inverse_block(sjd_flow *f, int block, const float *z_dev, float *x_dev, int batch,
+                             const sjd_jacobi_opts *opts, int32_t *iters_per_sample_host, int32_t *block_iters_host,
+                             void *hip_stream) {
+    int rc = check_call(f, block, z_dev, x_dev, batch);
+    if (rc) return rc;
+    if ((rc = check_opts(opts))) return rc;
+    hipStream_t s = (hipStream_t)hip_stream;
+    HIP_TRY(hipSetDevice(f->device));
+    int passes = 0;
+    bool nonfinite = false;
+    if ((rc = run_jacobi(f, block, z_dev, x_dev, batch, opts, &passes, &nonfinite, s))) return rc;
+    if (iters_per_sample_host) memcpy(iters_per_sample_host, f->host_pin + 2, sizeof(int32_t) * batch);
+    if (block_iters_host) *block_iters_host = passes;
+    if (nonfinite) return fail(SJD_ENONFINITE, "block %d: a sample ended with a non-finite difference norm", block);
+    return SJD_OK;
+}
+
+int sjd_sequential_inverse_block(sjd_flow *f, int block, const float *z_dev, float *x_dev, int batch,
+                                 void *hip_stream) {
+    int rc = check_call(f, block, z_dev, x_dev, batch);
+    if (rc) return rc;
+    hipStream_t s = (hipStream_t)hip_stream;
+    HIP_TRY(hipSetDevice(f->device));
+    if ((rc = run_sequential(f, block, z_dev, x_dev, batch, s))) return rc;
+    HIP_TRY(hipStreamSynchronize(s));
+    HIP_TRY(hipGetLastError());
+    return SJD_OK;
+}
+
+int sjd_sample(sjd_flow *f, const float *z_dev, float *x_dev, int batch, uint32_t jacobi_mask,
+               const sjd_jacobi_opts *opts, sjd_stats *stats_host, int32_t *iters_host, void *hip_stream) {
+    int rc = check_call(f, 0, z_dev, x_dev, batch);
+    if (rc) return rc;
+    const sjd_config &c = f->cfg;
+    uint32_t used = c.n_blocks >= 32 ? 0xFFFFFFFFu : ((1u << c.n_blocks) - 1u);
+    if ((jacobi_mask & used) && (rc = check_opts(opts))) return rc;
+    hipStream_t s = (hipStream_t)hip_stream;
+    HIP_TRY(hipSetDevice(f->device));
+    if (stats_host) memset(stats_host, 0, sizeof(*stats_host));
+    const int T = c.seq_len;
+    bool any_nonfinite = false;
+    const float *in = z_dev;
+    HIP_TRY(hipEventRecord(f->ev[0], s));
+    for (int j = 0; j < c.n_blocks; ++j) {
+        float *out = (j == c.n_blocks - 1) ? x_dev : f->pp[j & 1];
+        if ((jacobi_mask >> j) & 1u) {
+            int passes = 0;
+            bool nonfinite = false;
+            if ((rc = run_jacobi(f, j, in, out, batch, opts, &passes, &nonfinite, s))) return rc;
+            any_nonfinite |= nonfinite;
+            double sum = 0;
+            for (int b = 0; b < batch; ++b) sum += f->host_pin[2 + b];
+            if (iters_host) memcpy(iters_host + (size_t)j * batch, f->host_pin + 2, sizeof(int32_t) * batch);
+            if (stats_host) {
+                stats_host->block_iters[j] = passes;
+                stats_host->mean_sample_iters[j] = batch ? (float)(sum / batch) : 0.f;
+            }
+        } else {
+            if ((rc = run_sequential(f, j, in, out, batch, s))) return rc;
+            if (iters_host) for (int b = 0; b < batch; ++b) iters_host[(size_t)j * batch + b] = T - 1;
+            if (stats_host) { stats_host->block_iters[j] = T - 1; stats_host->mean_sample_iters[j] = (float)(T - 1); }
+        }
+        HIP_TRY(hipEventRecord(f->ev[j + 1], s));
+        in = out;
+    }
+    HIP_TRY(hipStreamSynchronize(s));
+    HIP_TRY(hipGetLastError());
+    if (stats_host)
+        for (int j = 0; j < c.n_blocks; ++j) HIP_TRY(hipEventElapsedTime(&stats_host->block_ms[j], f->ev[j], f->ev[j + 1]));
+    if (any_nonfinite) return fail(SJD_ENONFINITE, "a sample ended a Jacobi block with a non-finite difference norm");
+    return SJD_OK;
+}
+
+int sjd_profile_enable(sjd_flow *f, uint32_t family_mask) {
+    if (!f) return fail(SJD_EINVAL, "null flow handle");
+    f->prof_mask = family_mask & ((1u << SJD_PROF_FAMILIES) - 1u);
+    return SJD_OK;
+}
+
+int sjd_profile_read(sjd_flow *f, sjd_profile *out_host, int reset) {
+    if (!f || !out_host) return fail(SJD_EINVAL, "null argument");
+    int rc = drain_profile(f);
+    if (rc) return rc;
+    *out_host = f->prof;
+    if (reset) memset(&f->prof, 0, sizeof(f->prof));
+    return SJD_OK;
+}
+
+}  // extern "C"

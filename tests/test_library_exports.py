@@ -1,0 +1,56 @@
+"""The built HIP library loads and exports every entry point the header declares (no compute, CPU ok)."""
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "sjd.h")).read()
+    return sorted(set(re.findall(r"SJD_API[^;(]*?\b(sjd_\w+)\s*\(", text)))
+
+
+def test_header_declares_the_four_calls_of_the_method():
+    names = _declared()
+    for n in ("sjd_flow_load_weights", "sjd_jacobi_inverse_block", "sjd_sequential_inverse_block", "sjd_sample"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol():
+    import paper_2505_24791_amd as sjd
+    if not os.path.exists(sjd.LIB_PATH):
+        from paper_2505_24791_amd import build
+        build.build()
+    lib = sjd.load_library()
+    declared = _declared()
+    assert sorted(sjd.EXPORTS) == declared
+    for n in declared:
+        assert getattr(lib, n) is not None
+
+
+def test_create_rejects_bad_arguments_without_touching_a_device():
+    import ctypes as C
+    import paper_2505_24791_amd as sjd
+    lib = sjd.load_library()
+    h = C.c_void_p()
+    assert lib.sjd_flow_create(None, C.byref(h)) == sjd.SJD_EINVAL
+    bad = sjd.SjdConfig(0, 1, 64, 1, 4, 8, 4, 1, 0, 0)
+    assert lib.sjd_flow_create(C.byref(bad), C.byref(h)) == sjd.SJD_EINVAL
+    assert b"n_blocks" in lib.sjd_last_error()
+    bad = sjd.SjdConfig(1, 1, 96, 4, 4, 8, 4, 1, 1, 0)      # bf16 needs width % 64 == 0
+    assert lib.sjd_flow_create(C.byref(bad), C.byref(h)) == sjd.SJD_EINVAL
+    bad = sjd.SjdConfig(1, 1, 100, 3, 4, 8, 4, 1, 0, 0)     # width not a multiple of heads
+    assert lib.sjd_flow_create(C.byref(bad), C.byref(h)) == sjd.SJD_EINVAL
+
+
+def test_product_never_touches_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2505_24791_amd")
+    for dirpath, _, files in os.walk(pkg):
+        if "_build" in dirpath:
+            continue
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, fn)).read()
+                assert "oracle" not in text.lower() or fn == "__init__.py" and "oracle" not in text.lower(), fn
