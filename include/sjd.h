@@ -50,6 +50,9 @@ extern "C" {
 #define SJD_DTYPE_F32 0  /* everything float32 (correctness configuration) */
 #define SJD_DTYPE_BF16 1 /* bf16 weights, matrix operands, stored activations and KV cache; float32 state
                             (x, mu, alpha), residual stream, LayerNorm statistics, softmax, accumulators, delta */
+#define SJD_DTYPE_F16 2  /* as SJD_DTYPE_BF16 but every 16-bit operand is IEEE half: three more mantissa bits
+                            for the same matrix-core rate.  bf16-valued weights convert exactly (values below
+                            2^-14 in magnitude to within 2^-25). */
 
 #if defined(__GNUC__)
 #define SJD_API __attribute__((visibility("default")))
@@ -62,7 +65,7 @@ typedef struct sjd_flow sjd_flow; /* opaque */
 typedef struct {
     int32_t n_blocks;   /* K, 1..SJD_MAX_BLOCKS */
     int32_t n_layers;   /* N >= 1 */
-    int32_t width;      /* W, a multiple of n_heads; bf16 mode needs W % 64 == 0 */
+    int32_t width;      /* W, a multiple of n_heads; the 16-bit modes need W % 64 == 0 */
     int32_t n_heads;    /* H */
     int32_t mlp_ratio;  /* hidden = mlp_ratio * W */
     int32_t seq_len;    /* T >= 1 */
@@ -115,8 +118,8 @@ SJD_API int sjd_flow_create(const sjd_config *cfg, sjd_flow **out);
  *           ln2_g [W] ln2_b [W]  w_fc1 [W,R*W] b_fc1 [R*W]  w_fc2 [R*W,W] b_fc2 [W] }
  *     lnf_g [W] lnf_b [W]  w_head [W,2D] b_head [2D]          (head columns: [mu | alpha])
  * q, k, v are the three W-wide column groups of w_qkv; head h owns columns h*dh..(h+1)*dh of each.
- * nbytes must equal the size that layout implies, else SJD_EINVAL.  In bf16 mode matrices are
- * rounded to bf16 (nearest even) on load.  The blob is not referenced after the call returns. */
+ * nbytes must equal the size that layout implies, else SJD_EINVAL.  In the 16-bit modes matrices
+ * are rounded to that type (nearest even) on load.  The blob is not referenced after the call returns. */
 SJD_API int sjd_flow_load_weights(sjd_flow *flow, const void *host_blob, size_t nbytes);
 
 /* Jacobi decoding of block `block` (Sec. 3.3, Alg. 1; iteration map of App. B, Def. A.1):

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libsjd.so")
 
 SJD_OK, SJD_EINVAL, SJD_ENOMEM, SJD_EHIP, SJD_ENONFINITE, SJD_ESTATE = 0, -1, -2, -3, -4, -5
 SJD_MAX_BLOCKS = 32
-DTYPE_F32, DTYPE_BF16 = 0, 1
+DTYPE_F32, DTYPE_BF16, DTYPE_F16 = 0, 1, 2
 PROF_GEMM, PROF_ATTENTION, PROF_EPILOGUE, PROF_DECODE_GEMM, PROF_DECODE_ATTN, PROF_OTHER = range(6)
 PROF_FAMILIES = 6
 PROF_NAMES = ("gemm", "attention", "epilogue", "decode_gemm", "decode_attn", "other")
@@ -125,7 +125,9 @@ class Flow:
         self.lib = load_library()
         self.cfg = cfg
         self.max_batch = int(max_batch if max_batch is not None else cfg.batch)
-        self.dtype = (DTYPE_BF16 if cfg.bf16 else DTYPE_F32) if dtype is None else dtype
+        # 16-bit workloads default to IEEE-half operands: their bf16-valued weights convert exactly and
+        # the activations keep three more mantissa bits, which the stopping rule needs (tau ~ 1e-3)
+        self.dtype = (DTYPE_F16 if cfg.bf16 else DTYPE_F32) if dtype is None else dtype
         c = SjdConfig(cfg.n_blocks, cfg.n_layers, cfg.width, cfg.n_heads, cfg.mlp_ratio, cfg.seq_len, cfg.token_dim,
                       self.max_batch, self.dtype, cfg.reverse_mask)
         h = C.c_void_p()

@@ -1,10 +1,10 @@
 // Causal multi-head attention.
 //
 //  * attention_rows_kernel: one wave per (sample, head, query row), any head size and sequence
-//    length, float32 or bf16 storage, float32 arithmetic.  It serves the float32 configuration's
+//    length, float32, bf16 or f16 storage, float32 arithmetic.  It serves the float32 configuration's
 //    whole-sequence passes and, with a key/value cache, every single-token step of the sequential
 //    inverse (Sec. 3.5), where it is bound by reading the cached prefix from HBM.
-//  * flash_attention_bf16_kernel: whole-sequence causal attention for head size 64 on bf16 with
+//  * flash_attention_h16_kernel: whole-sequence causal attention for head size 64 on 16-bit data with
 //    MFMA; K tiles and transposed V tiles are staged in LDS, scores never leave registers
 //    (online softmax in float32), so there is no T x T buffer.
 #include "common.h"
@@ -100,6 +100,8 @@ template void launch_attention_rows<float, float>(const float *, int64_t, const 
                                                   int64_t, float *, int64_t, int, int, int, int, int, hipStream_t);
 template void launch_attention_rows<bf16, bf16>(const bf16 *, int64_t, const bf16 *, const bf16 *, int64_t, int64_t,
                                                 bf16 *, int64_t, int, int, int, int, int, hipStream_t);
+template void launch_attention_rows<f16, f16>(const f16 *, int64_t, const f16 *, const f16 *, int64_t, int64_t, f16 *,
+                                              int64_t, int, int, int, int, int, hipStream_t);
 
 template <typename AT>
 void launch_decode_attention(const AT *qkv, AT *kcache, AT *vcache, AT *o, int B, int T, int t, int H, int dh,
@@ -116,6 +118,7 @@ void launch_decode_attention(const AT *qkv, AT *kcache, AT *vcache, AT *o, int B
 template void launch_decode_attention<float>(const float *, float *, float *, float *, int, int, int, int, int,
                                              hipStream_t);
 template void launch_decode_attention<bf16>(const bf16 *, bf16 *, bf16 *, bf16 *, int, int, int, int, int, hipStream_t);
+template void launch_decode_attention<f16>(const f16 *, f16 *, f16 *, f16 *, int, int, int, int, int, hipStream_t);
 
 // ------------------------------------------------------------------------------------------------
 // Flash-style kernel, head size 64.  A workgroup (4 waves) owns 128 query rows of one
@@ -124,29 +127,32 @@ template void launch_decode_attention<bf16>(const bf16 *, bf16 *, bf16 *, bf16 *
 // lane-local plus one cross-half exchange, and the probabilities are already laid out as the
 // B operand of the second product O^T = V^T P^T (16 keys per instruction).
 constexpr int FA_BQ = 128, FA_BK = 64, FA_DH = 64;
-constexpr int FA_KS = FA_DH + 8;   // K tile row stride (bf16)
-constexpr int FA_VS = FA_BK + 8;   // V^T tile row stride (bf16)
+constexpr int FA_KS = FA_DH + 8;   // K tile row stride (elements)
+constexpr int FA_VS = FA_BK + 8;   // V^T tile row stride (elements)
 
-__global__ __launch_bounds__(256) void flash_attention_bf16_kernel(const bf16 *__restrict__ qkv, bf16 *__restrict__ o,
-                                                                   int T, int H, float scale_log2) {
-    __shared__ __attribute__((aligned(16))) bf16 Ks[FA_BK * FA_KS];
-    __shared__ __attribute__((aligned(16))) bf16 Vt[FA_DH * FA_VS];
+template <typename HT>
+__global__ __launch_bounds__(256) void flash_attention_h16_kernel(const HT *__restrict__ qkv, HT *__restrict__ o,
+                                                                  int T, int H, float scale_log2) {
+    typedef typename Half16<HT>::v8 v8;
+    typedef typename Half16<HT>::v4 v4;
+    __shared__ __attribute__((aligned(16))) HT Ks[FA_BK * FA_KS];
+    __shared__ __attribute__((aligned(16))) HT Vt[FA_DH * FA_VS];
     const int W = H * FA_DH;
     const int n_qt = (T + FA_BQ - 1) / FA_BQ;
     const int qt = n_qt - 1 - (int)blockIdx.x;  // heavy tiles first
     const int h = blockIdx.y, i = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, g = lane >> 5;
-    const bf16 *base = qkv + (size_t)i * T * 3 * W;
+    const HT *base = qkv + (size_t)i * T * 3 * W;
     const int q0 = qt * FA_BQ + wave * 32;      // first query row of this wave
     const int qrow = q0 + l32;                  // this lane's query row
     const int qrow_c = qrow < T ? qrow : T - 1;
 
     // Q^T as B operand: lane (q = l32, g) holds Q[q][16c + 8g .. +7] for the four 16-wide chunks of dh
-    bf16x8 qf[4];
+    v8 qf[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c)
-        qf[c] = *reinterpret_cast<const bf16x8 *>(base + (size_t)qrow_c * 3 * W + h * FA_DH + 16 * c + 8 * g);
+        qf[c] = *reinterpret_cast<const v8 *>(base + (size_t)qrow_c * 3 * W + h * FA_DH + 16 * c + 8 * g);
 
     f32x16 oacc[2];
 #pragma unroll
@@ -167,10 +173,10 @@ __global__ __launch_bounds__(256) void flash_attention_bf16_kernel(const bf16 *_
             const int key = c >> 3, dc = c & 7;
             int krow = key0 + key;
             krow = krow < T ? krow : T - 1;
-            const bf16 *src = base + (size_t)krow * 3 * W + h * FA_DH + dc * 8;
-            const bf16x8 kv8 = *reinterpret_cast<const bf16x8 *>(src + W);
-            const bf16x8 vv8 = *reinterpret_cast<const bf16x8 *>(src + 2 * W);
-            *reinterpret_cast<bf16x8 *>(&Ks[key * FA_KS + dc * 8]) = kv8;
+            const HT *src = base + (size_t)krow * 3 * W + h * FA_DH + dc * 8;
+            const v8 kv8 = *reinterpret_cast<const v8 *>(src + W);
+            const v8 vv8 = *reinterpret_cast<const v8 *>(src + 2 * W);
+            *reinterpret_cast<v8 *>(&Ks[key * FA_KS + dc * 8]) = kv8;
 #pragma unroll
             for (int e = 0; e < 8; ++e) Vt[(dc * 8 + e) * FA_VS + key] = vv8[e];
         }
@@ -185,8 +191,8 @@ __global__ __launch_bounds__(256) void flash_attention_bf16_kernel(const bf16 *_
             for (int v = 0; v < 16; ++v) sacc[kb][v] = 0.f;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(&Ks[(32 * kb + l32) * FA_KS + 16 * c + 8 * g]);
-                sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[c], sacc[kb], 0, 0, 0);
+                const v8 kf = *reinterpret_cast<const v8 *>(&Ks[(32 * kb + l32) * FA_KS + 16 * c + 8 * g]);
+                sacc[kb] = Half16<HT>::mfma(kf, qf[c], sacc[kb]);
             }
         }
         // register v of block kb is key key0 + 32 kb + 8 (v/4) + 4 g + v%4, query qrow
@@ -229,42 +235,45 @@ __global__ __launch_bounds__(256) void flash_attention_bf16_kernel(const bf16 *_
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int c2 = 0; c2 < 2; ++c2) {
-                bf16x8 pf;
+                v8 pf;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) pf[e] = (bf16)sacc[kb][8 * c2 + e];
+                for (int e = 0; e < 8; ++e) pf[e] = from_f32<HT>(sacc[kb][8 * c2 + e]);
 #pragma unroll
                 for (int db = 0; db < 2; ++db) {
-                    const bf16 *vrow = &Vt[(32 * db + l32) * FA_VS + 32 * kb + 16 * c2 + 4 * g];
-                    const bf16x4 lo = *reinterpret_cast<const bf16x4 *>(vrow);
-                    const bf16x4 hi = *reinterpret_cast<const bf16x4 *>(vrow + 8);
-                    bf16x8 vf;
+                    const HT *vrow = &Vt[(32 * db + l32) * FA_VS + 32 * kb + 16 * c2 + 4 * g];
+                    const v4 lo = *reinterpret_cast<const v4 *>(vrow);
+                    const v4 hi = *reinterpret_cast<const v4 *>(vrow + 8);
+                    v8 vf;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) { vf[e] = lo[e]; vf[4 + e] = hi[e]; }
-                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[db], 0, 0, 0);
+                    oacc[db] = Half16<HT>::mfma(vf, pf, oacc[db]);
                 }
             }
     }
     // O^T block db: register v is d = 32 db + 8 (v/4) + 4 g + v%4, query qrow
     if (qrow < T) {
         const float inv = 1.0f / l_run;
-        bf16 *orow = o + ((size_t)i * T + qrow) * W + h * FA_DH;
+        HT *orow = o + ((size_t)i * T + qrow) * W + h * FA_DH;
 #pragma unroll
         for (int db = 0; db < 2; ++db)
 #pragma unroll
             for (int a = 0; a < 4; ++a) {
-                bf16x4 ov;
+                v4 ov;
 #pragma unroll
-                for (int b = 0; b < 4; ++b) ov[b] = (bf16)(oacc[db][4 * a + b] * inv);
-                *reinterpret_cast<bf16x4 *>(orow + 32 * db + 8 * a + 4 * g) = ov;
+                for (int b = 0; b < 4; ++b) ov[b] = from_f32<HT>(oacc[db][4 * a + b] * inv);
+                *reinterpret_cast<v4 *>(orow + 32 * db + 8 * a + 4 * g) = ov;
             }
     }
 }
 
-void launch_flash_attention_bf16(const bf16 *qkv, bf16 *o, int n_samples, int T, int H, hipStream_t s) {
+template <typename HT>
+void launch_flash_attention_h16(const HT *qkv, HT *o, int n_samples, int T, int H, hipStream_t s) {
     if (n_samples <= 0) return;
     const int n_qt = (T + FA_BQ - 1) / FA_BQ;
     const float scale_log2 = 1.4426950408889634f / sqrtf((float)FA_DH);
-    hipLaunchKernelGGL(flash_attention_bf16_kernel, dim3(n_qt, H, n_samples), dim3(256), 0, s, qkv, o, T, H, scale_log2);
+    hipLaunchKernelGGL(flash_attention_h16_kernel<HT>, dim3(n_qt, H, n_samples), dim3(256), 0, s, qkv, o, T, H, scale_log2);
 }
+template void launch_flash_attention_h16<bf16>(const bf16 *, bf16 *, int, int, int, hipStream_t);
+template void launch_flash_attention_h16<f16>(const f16 *, f16 *, int, int, int, hipStream_t);
 
 }  // namespace sjd

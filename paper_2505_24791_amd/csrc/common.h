@@ -9,6 +9,9 @@ namespace sjd {
 typedef __bf16 bf16;
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16;
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
@@ -28,9 +31,29 @@ __device__ __forceinline__ float wave_max(float v) {
 template <typename T> __device__ __forceinline__ float to_f32(T v);
 template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ float to_f32<bf16>(bf16 v) { return (float)v; }
+template <> __device__ __forceinline__ float to_f32<f16>(f16 v) { return (float)v; }
 template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ f16 from_f32<f16>(float v) { return (f16)v; }
 template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return (bf16)v; }
+
+// The two 16-bit operand types of the MFMA kernels: vectors of 4 / 8 elements and the
+// 32x32x16 matrix instruction with float32 accumulation.
+template <typename HT> struct Half16;
+template <> struct Half16<bf16> {
+    typedef bf16x4 v4;
+    typedef bf16x8 v8;
+    static __device__ __forceinline__ f32x16 mfma(v8 a, v8 b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    }
+};
+template <> struct Half16<f16> {
+    typedef f16x4 v4;
+    typedef f16x8 v8;
+    static __device__ __forceinline__ f32x16 mfma(v8 a, v8 b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+    }
+};
 
 __device__ __forceinline__ float gelu_erf(float v) { return 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f)); }
 
@@ -57,7 +80,7 @@ enum Epi : int {
 void launch_embed(const float *x, const float *w_in, const float *b_in, const float *pos, float *h, int n_rows,
                   int D, int W, RowMap map, hipStream_t s);
 
-// y = LayerNorm(x) * g + b over rows of width W (biased variance, eps 1e-5); OutT float or bf16
+// y = LayerNorm(x) * g + b over rows of width W (biased variance, eps 1e-5); OutT float, bf16 or f16
 template <typename OutT>
 void launch_layernorm(const float *x, const float *g, const float *b, OutT *y, int n_rows, int W, hipStream_t s);
 
@@ -65,12 +88,12 @@ void launch_layernorm(const float *x, const float *g, const float *b, OutT *y, i
 void launch_gemm_f32(const float *A, const float *B, const float *bias, const float *resid, float *C, int M, int N,
                      int K, Epi epi, hipStream_t s);
 
-// bf16 MFMA projection: C[M,N] = epi(A[M,K] * Bt[N,K]^T + bias); Bt holds the weight transposed with
-// rows padded to `ldb` (>= K) and at least round_up(N, 128) rows (zero filled).  K % 64 == 0.
-// OutT bf16 (EPI_BIAS, EPI_BIAS_GELU) or float (EPI_BIAS, EPI_BIAS_RESIDUAL).
-template <typename OutT>
-void launch_gemm_bf16(const bf16 *A, const bf16 *Bt, const float *bias, const float *resid, OutT *C, int M, int N,
-                      int K, Epi epi, hipStream_t s);
+// 16-bit MFMA projection (HT = bf16 or f16): C[M,N] = epi(A[M,K] * Bt[N,K]^T + bias); Bt holds the
+// weight transposed, K contiguous, with at least round_up(N, 256) rows (zero filled).  K % 64 == 0.
+// OutT = HT (EPI_BIAS, EPI_BIAS_GELU) or float (EPI_BIAS, EPI_BIAS_RESIDUAL).
+template <typename HT, typename OutT>
+void launch_gemm_h16(const HT *A, const HT *Bt, const float *bias, const float *resid, OutT *C, int M, int N, int K,
+                     Epi epi, hipStream_t s);
 
 // Causal attention, one wave per (sample, head, query row); works for any shape and both types.
 // q rows: q + (sample*q_rows_per_sample + r) * q_stride; row r (processing position t0 + r) attends
@@ -87,8 +110,9 @@ template <typename AT>
 void launch_decode_attention(const AT *qkv, AT *kcache, AT *vcache, AT *o, int B, int T, int t, int H, int dh,
                              hipStream_t s);
 
-// Flash-style causal attention on bf16 qkv [n_samples*T, 3W] (head dim 64), o [n_samples*T, W].
-void launch_flash_attention_bf16(const bf16 *qkv, bf16 *o, int n_samples, int T, int H, hipStream_t s);
+// Flash-style causal attention on 16-bit qkv [n_samples*T, 3W] (head size 64), o [n_samples*T, W].
+template <typename HT>
+void launch_flash_attention_h16(const HT *qkv, HT *o, int n_samples, int T, int H, hipStream_t s);
 
 // Jacobi epilogue.  p [n_rows, 2D] head output (row r of a sample parameterises position r+1).
 // For every listed sample that is still active: x <- z*exp(alpha)+mu in place, delta, pass count,
@@ -117,7 +141,8 @@ void launch_decode_epilogue(const float *p, const float *z, float *x, int B, int
 // mu/alpha extraction for sjd_conditioner: shifted parameters in canonical order.
 void launch_split_params(const float *p, float *mu, float *alpha, int B, int T, int D, int reversed, hipStream_t s);
 
-// Weight preparation on the device: dst[n, k] (bf16, row length ldb, zero padded) = src[k, n] (float [K, N]).
-void launch_transpose_to_bf16(const float *src, bf16 *dst, int K, int N, int ldb, int n_rows_padded, hipStream_t s);
+// Weight preparation on the device: dst[n, k] (16-bit, row length ldb, zero padded) = src[k, n] (float [K, N]).
+template <typename HT>
+void launch_transpose_to_h16(const float *src, HT *dst, int K, int N, int ldb, int n_rows_padded, hipStream_t s);
 
 }  // namespace sjd

@@ -60,6 +60,7 @@ void launch_layernorm(const float *x, const float *g, const float *b, OutT *y, i
 }
 template void launch_layernorm<float>(const float *, const float *, const float *, float *, int, int, hipStream_t);
 template void launch_layernorm<bf16>(const float *, const float *, const float *, bf16 *, int, int, hipStream_t);
+template void launch_layernorm<f16>(const float *, const float *, const float *, f16 *, int, int, hipStream_t);
 
 // ------------------------------------------------------------------------------------------------
 // Jacobi epilogue (Alg. 1, the update line and the stopping test; F of Def. A.1).
@@ -219,9 +220,10 @@ void launch_split_params(const float *p, float *mu, float *alpha, int B, int T, 
 }
 
 // ------------------------------------------------------------------------------------------------
-// dst[n, k] = bf16(src[k, n]) for n < N, k < K; zero elsewhere (rows up to n_rows_padded, row length ldb)
-__global__ __launch_bounds__(256) void transpose_to_bf16_kernel(const float *__restrict__ src, bf16 *__restrict__ dst,
-                                                                int K, int N, int ldb, int n_rows_padded) {
+// dst[n, k] = HT(src[k, n]) for n < N, k < K; zero elsewhere (rows up to n_rows_padded, row length ldb)
+template <typename HT>
+__global__ __launch_bounds__(256) void transpose_to_h16_kernel(const float *__restrict__ src, HT *__restrict__ dst,
+                                                               int K, int N, int ldb, int n_rows_padded) {
     __shared__ float tile[32][33];
     const int k0 = blockIdx.x * 32, n0 = blockIdx.y * 32;
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
@@ -232,13 +234,16 @@ __global__ __launch_bounds__(256) void transpose_to_bf16_kernel(const float *__r
     __syncthreads();
     for (int r = ty; r < 32; r += 8) {
         const int n = n0 + r, k = k0 + tx;
-        if (n < n_rows_padded && k < ldb) dst[(size_t)n * ldb + k] = (bf16)tile[tx][r];
+        if (n < n_rows_padded && k < ldb) dst[(size_t)n * ldb + k] = from_f32<HT>(tile[tx][r]);
     }
 }
 
-void launch_transpose_to_bf16(const float *src, bf16 *dst, int K, int N, int ldb, int n_rows_padded, hipStream_t s) {
+template <typename HT>
+void launch_transpose_to_h16(const float *src, HT *dst, int K, int N, int ldb, int n_rows_padded, hipStream_t s) {
     dim3 grid((ldb + 31) / 32, (n_rows_padded + 31) / 32);
-    hipLaunchKernelGGL(transpose_to_bf16_kernel, grid, dim3(256), 0, s, src, dst, K, N, ldb, n_rows_padded);
+    hipLaunchKernelGGL(transpose_to_h16_kernel<HT>, grid, dim3(256), 0, s, src, dst, K, N, ldb, n_rows_padded);
 }
+template void launch_transpose_to_h16<bf16>(const float *, bf16 *, int, int, int, int, hipStream_t);
+template void launch_transpose_to_h16<f16>(const float *, f16 *, int, int, int, int, hipStream_t);
 
 }  // namespace sjd

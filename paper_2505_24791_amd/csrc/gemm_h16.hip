@@ -1,7 +1,7 @@
-// bf16 MFMA projection with float32 accumulation: C[M,N] = epi(A[M,K] * Bt[N,K]^T + bias).
+// 16-bit (bf16 or f16 operands) MFMA projection with float32 accumulation: C[M,N] = epi(A[M,K] * Bt[N,K]^T + bias).
 //
 // Both operands are K-contiguous (the weights are stored transposed at load time), which is the
-// shape v_mfma_f32_32x32x16_bf16 wants: every lane feeds 8 consecutive k of one row.  A workgroup
+// shape v_mfma_f32_32x32x16_{bf16,f16} wants: every lane feeds 8 consecutive k of one row.  A workgroup
 // of four waves (2 x 2) owns a BM x BN tile; a wave owns (BM/2) x (BN/2) as 32x32 MFMA blocks.
 // K is walked in index order in steps of 64 through LDS (rows padded by 16 bytes against bank
 // conflicts), the next step's global loads being in flight while the current one is multiplied.
@@ -15,16 +15,17 @@ constexpr int G_BK = 64;
 constexpr int G_PAD = 8;
 constexpr int G_LDS_STRIDE = G_BK + G_PAD;  // in bf16 elements
 
-template <int BM, int BN, typename OutT, int EPI>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ Bt,
+template <typename HT, int BM, int BN, typename OutT, int EPI>
+__global__ __launch_bounds__(256) void gemm_h16_kernel(const HT *__restrict__ A, const HT *__restrict__ Bt,
                                                         const float *__restrict__ bias, const float *resid, OutT *C,
                                                         int M, int N, int K, int tiles_n) {
     constexpr int MI = BM / 64, NI = BN / 64;    // 32x32 blocks per wave in each direction
     constexpr int A_CHUNKS = BM * 8 / 256;        // 16-byte chunks per thread per k-step
     constexpr int B_CHUNKS = BN * 8 / 256;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    bf16 *As = reinterpret_cast<bf16 *>(smem_raw);
-    bf16 *Bs = As + BM * G_LDS_STRIDE;
+    typedef typename Half16<HT>::v8 v8;
+    HT *As = reinterpret_cast<HT *>(smem_raw);
+    HT *Bs = As + BM * G_LDS_STRIDE;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -43,9 +44,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16 *__restrict__
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     // global -> register staging: chunk c covers row c/8, k offset 8*(c%8)
-    bf16x8 ra[A_CHUNKS], rb[B_CHUNKS];
-    const bf16 *a_ptr[A_CHUNKS];
-    const bf16 *b_ptr[B_CHUNKS];
+    v8 ra[A_CHUNKS], rb[B_CHUNKS];
+    const HT *a_ptr[A_CHUNKS];
+    const HT *b_ptr[B_CHUNKS];
 #pragma unroll
     for (int r = 0; r < A_CHUNKS; ++r) {
         const int c = tid + r * 256;
@@ -59,43 +60,43 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16 *__restrict__
         b_ptr[r] = Bt + (size_t)(n0 + (c >> 3)) * K + (c & 7) * 8;  // Bt rows are padded up to the tile
     }
 #pragma unroll
-    for (int r = 0; r < A_CHUNKS; ++r) ra[r] = *reinterpret_cast<const bf16x8 *>(a_ptr[r]);
+    for (int r = 0; r < A_CHUNKS; ++r) ra[r] = *reinterpret_cast<const v8 *>(a_ptr[r]);
 #pragma unroll
-    for (int r = 0; r < B_CHUNKS; ++r) rb[r] = *reinterpret_cast<const bf16x8 *>(b_ptr[r]);
+    for (int r = 0; r < B_CHUNKS; ++r) rb[r] = *reinterpret_cast<const v8 *>(b_ptr[r]);
 
     const int KT = K / G_BK;
     for (int kt = 0; kt < KT; ++kt) {
 #pragma unroll
         for (int r = 0; r < A_CHUNKS; ++r) {
             const int c = tid + r * 256;
-            *reinterpret_cast<bf16x8 *>(&As[(c >> 3) * G_LDS_STRIDE + (c & 7) * 8]) = ra[r];
+            *reinterpret_cast<v8 *>(&As[(c >> 3) * G_LDS_STRIDE + (c & 7) * 8]) = ra[r];
         }
 #pragma unroll
         for (int r = 0; r < B_CHUNKS; ++r) {
             const int c = tid + r * 256;
-            *reinterpret_cast<bf16x8 *>(&Bs[(c >> 3) * G_LDS_STRIDE + (c & 7) * 8]) = rb[r];
+            *reinterpret_cast<v8 *>(&Bs[(c >> 3) * G_LDS_STRIDE + (c & 7) * 8]) = rb[r];
         }
         __syncthreads();
         if (kt + 1 < KT) {
 #pragma unroll
-            for (int r = 0; r < A_CHUNKS; ++r) ra[r] = *reinterpret_cast<const bf16x8 *>(a_ptr[r] + (size_t)(kt + 1) * G_BK);
+            for (int r = 0; r < A_CHUNKS; ++r) ra[r] = *reinterpret_cast<const v8 *>(a_ptr[r] + (size_t)(kt + 1) * G_BK);
 #pragma unroll
-            for (int r = 0; r < B_CHUNKS; ++r) rb[r] = *reinterpret_cast<const bf16x8 *>(b_ptr[r] + (size_t)(kt + 1) * G_BK);
+            for (int r = 0; r < B_CHUNKS; ++r) rb[r] = *reinterpret_cast<const v8 *>(b_ptr[r] + (size_t)(kt + 1) * G_BK);
         }
 #pragma unroll
         for (int ks = 0; ks < G_BK / 16; ++ks) {
-            bf16x8 fa[MI], fb[NI];
+            v8 fa[MI], fb[NI];
 #pragma unroll
             for (int i = 0; i < MI; ++i)
-                fa[i] = *reinterpret_cast<const bf16x8 *>(&As[(wm0 + 32 * i + l32) * G_LDS_STRIDE + ks * 16 + 8 * g]);
+                fa[i] = *reinterpret_cast<const v8 *>(&As[(wm0 + 32 * i + l32) * G_LDS_STRIDE + ks * 16 + 8 * g]);
 #pragma unroll
             for (int j = 0; j < NI; ++j)
-                fb[j] = *reinterpret_cast<const bf16x8 *>(&Bs[(wn0 + 32 * j + l32) * G_LDS_STRIDE + ks * 16 + 8 * g]);
+                fb[j] = *reinterpret_cast<const v8 *>(&Bs[(wn0 + 32 * j + l32) * G_LDS_STRIDE + ks * 16 + 8 * g]);
 #pragma unroll
             for (int i = 0; i < MI; ++i)
 #pragma unroll
                 for (int j = 0; j < NI; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = Half16<HT>::mfma(fa[i], fb[j], acc[i][j]);
         }
         __syncthreads();
     }
@@ -121,12 +122,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16 *__restrict__
     }
 }
 
-template <int BM, int BN, typename OutT, int EPI>
-static void launch_tile(const bf16 *A, const bf16 *Bt, const float *bias, const float *resid, OutT *C, int M, int N,
+template <typename HT, int BM, int BN, typename OutT, int EPI>
+static void launch_tile(const HT *A, const HT *Bt, const float *bias, const float *resid, OutT *C, int M, int N,
                         int K, hipStream_t s) {
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    const size_t smem = (size_t)(BM + BN) * G_LDS_STRIDE * sizeof(bf16);
-    auto kern = gemm_bf16_kernel<BM, BN, OutT, EPI>;
+    const size_t smem = (size_t)(BM + BN) * G_LDS_STRIDE * sizeof(HT);
+    auto kern = gemm_h16_kernel<HT, BM, BN, OutT, EPI>;
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -135,26 +136,31 @@ static void launch_tile(const bf16 *A, const bf16 *Bt, const float *bias, const 
     hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(256), smem, s, A, Bt, bias, resid, C, M, N, K, tiles_n);
 }
 
-template <typename OutT, int EPI>
-static void pick_tile(const bf16 *A, const bf16 *Bt, const float *bias, const float *resid, OutT *C, int M, int N,
+template <typename HT, typename OutT, int EPI>
+static void pick_tile(const HT *A, const HT *Bt, const float *bias, const float *resid, OutT *C, int M, int N,
                       int K, hipStream_t s) {
-    launch_tile<128, 128, OutT, EPI>(A, Bt, bias, resid, C, M, N, K, s);
+    launch_tile<HT, 128, 128, OutT, EPI>(A, Bt, bias, resid, C, M, N, K, s);
 }
 
-template <>
-void launch_gemm_bf16<bf16>(const bf16 *A, const bf16 *Bt, const float *bias, const float *resid, bf16 *C, int M,
-                            int N, int K, Epi epi, hipStream_t s) {
+template <typename HT, typename OutT>
+void launch_gemm_h16(const HT *A, const HT *Bt, const float *bias, const float *resid, OutT *C, int M, int N, int K,
+                     Epi epi, hipStream_t s) {
     if (M <= 0 || N <= 0) return;
-    if (epi == EPI_BIAS_GELU) pick_tile<bf16, EPI_BIAS_GELU>(A, Bt, bias, resid, C, M, N, K, s);
-    else pick_tile<bf16, EPI_BIAS>(A, Bt, bias, resid, C, M, N, K, s);
+    if constexpr (sizeof(OutT) == 4) {
+        if (epi == EPI_BIAS_RESIDUAL) pick_tile<HT, float, EPI_BIAS_RESIDUAL>(A, Bt, bias, resid, C, M, N, K, s);
+        else pick_tile<HT, float, EPI_BIAS>(A, Bt, bias, resid, C, M, N, K, s);
+    } else {
+        if (epi == EPI_BIAS_GELU) pick_tile<HT, HT, EPI_BIAS_GELU>(A, Bt, bias, resid, C, M, N, K, s);
+        else pick_tile<HT, HT, EPI_BIAS>(A, Bt, bias, resid, C, M, N, K, s);
+    }
 }
-
-template <>
-void launch_gemm_bf16<float>(const bf16 *A, const bf16 *Bt, const float *bias, const float *resid, float *C, int M,
-                             int N, int K, Epi epi, hipStream_t s) {
-    if (M <= 0 || N <= 0) return;
-    if (epi == EPI_BIAS_RESIDUAL) pick_tile<float, EPI_BIAS_RESIDUAL>(A, Bt, bias, resid, C, M, N, K, s);
-    else pick_tile<float, EPI_BIAS>(A, Bt, bias, resid, C, M, N, K, s);
-}
+template void launch_gemm_h16<bf16, bf16>(const bf16 *, const bf16 *, const float *, const float *, bf16 *, int, int,
+                                          int, Epi, hipStream_t);
+template void launch_gemm_h16<bf16, float>(const bf16 *, const bf16 *, const float *, const float *, float *, int, int,
+                                           int, Epi, hipStream_t);
+template void launch_gemm_h16<f16, f16>(const f16 *, const f16 *, const float *, const float *, f16 *, int, int, int,
+                                        Epi, hipStream_t);
+template void launch_gemm_h16<f16, float>(const f16 *, const f16 *, const float *, const float *, float *, int, int,
+                                          int, Epi, hipStream_t);
 
 }  // namespace sjd

@@ -37,11 +37,11 @@ int fail(int code, const char *fmt, ...) {
 struct LayerW {
     const float *ln1_g, *ln1_b, *b_qkv, *b_o, *ln2_g, *ln2_b, *b_fc1, *b_fc2;
     const float *w_qkv, *w_o, *w_fc1, *w_fc2;      // float32 [in, out] (views into the device blob)
-    bf16 *t_qkv, *t_o, *t_fc1, *t_fc2;             // bf16 transposed [out (padded), in]
+    void *t_qkv, *t_o, *t_fc1, *t_fc2;             // 16-bit transposed [out (padded), in]
 };
 struct BlockW {
     const float *w_in, *b_in, *pos, *lnf_g, *lnf_b, *w_head, *b_head;
-    bf16 *t_head;
+    void *t_head;
     std::vector<LayerW> layer;
 };
 
@@ -56,7 +56,7 @@ struct sjd_flow {
     size_t bytes = 0;
     std::vector<void *> allocs;
     float *blob = nullptr;       // whole float32 blob on the device
-    bf16 *arena = nullptr;       // transposed bf16 matrices
+    void *arena = nullptr;       // transposed 16-bit matrices
     std::vector<BlockW> block;
     // workspaces (element type depends on dtype: float or bf16 for a, qkv, o, f and the cache)
     float *h = nullptr, *p = nullptr;
@@ -76,7 +76,7 @@ struct sjd_flow {
 
 namespace {
 
-size_t act_bytes(const sjd_flow *f) { return f->cfg.dtype == SJD_DTYPE_BF16 ? 2 : 4; }
+size_t act_bytes(const sjd_flow *f) { return f->cfg.dtype == SJD_DTYPE_F32 ? 4 : 2; }
 
 int dev_alloc(sjd_flow *f, void **out, size_t nbytes) {
     if (nbytes == 0) nbytes = 256;
@@ -144,30 +144,55 @@ int drain_profile(sjd_flow *f) {
 }
 
 // ---- one projection, in the flow's precision ----------------------------------------------------
+template <typename HT>
+void project16(const void *A, const void *wt, const float *bias, void *C, int M, int N, int K, Epi epi, bool out_f32,
+               hipStream_t s) {
+    if (out_f32)
+        launch_gemm_h16<HT, float>((const HT *)A, (const HT *)wt, bias,
+                                   epi == EPI_BIAS_RESIDUAL ? (const float *)C : nullptr, (float *)C, M, N, K, epi, s);
+    else
+        launch_gemm_h16<HT, HT>((const HT *)A, (const HT *)wt, bias, nullptr, (HT *)C, M, N, K, epi, s);
+}
+
 // in: A [M, K]; out: C [M, N]; residual variant accumulates into the float32 stream h in place.
-void project(sjd_flow *f, int fam, const void *A, const float *w32, const bf16 *wt, const float *bias, void *C, int M,
+void project(sjd_flow *f, int fam, const void *A, const float *w32, const void *wt, const float *bias, void *C, int M,
              int N, int K, Epi epi, bool out_f32, hipStream_t s) {
-    const bool bf = f->cfg.dtype == SJD_DTYPE_BF16;
-    const double in_b = bf ? 2.0 : 4.0, out_b = (bf && !out_f32) ? 2.0 : 4.0;
+    const int dt = f->cfg.dtype;
+    const double in_b = dt == SJD_DTYPE_F32 ? 4.0 : 2.0, out_b = (dt != SJD_DTYPE_F32 && !out_f32) ? 2.0 : 4.0;
     double bytes = (double)M * K * in_b + (double)K * N * in_b + (double)M * N * out_b + (double)N * 4;
     if (epi == EPI_BIAS_RESIDUAL) bytes += (double)M * N * 4;
     ProfScope ps(f, fam, 2.0 * M * (double)N * K, bytes, s);
-    if (!bf) {
+    if (dt == SJD_DTYPE_F32)
         launch_gemm_f32((const float *)A, w32, bias, epi == EPI_BIAS_RESIDUAL ? (const float *)C : nullptr, (float *)C,
                         M, N, K, epi, s);
-    } else if (out_f32) {
-        launch_gemm_bf16<float>((const bf16 *)A, wt, bias, epi == EPI_BIAS_RESIDUAL ? (const float *)C : nullptr,
-                                (float *)C, M, N, K, epi, s);
-    } else {
-        launch_gemm_bf16<bf16>((const bf16 *)A, wt, bias, nullptr, (bf16 *)C, M, N, K, epi, s);
-    }
+    else if (dt == SJD_DTYPE_BF16) project16<bf16>(A, wt, bias, C, M, N, K, epi, out_f32, s);
+    else project16<f16>(A, wt, bias, C, M, N, K, epi, out_f32, s);
 }
 
 void layernorm(sjd_flow *f, const float *x, const float *g, const float *b, void *y, int rows, hipStream_t s) {
     const int W = f->cfg.width;
     ProfScope ps(f, SJD_PROF_OTHER, 0.0, (double)rows * W * (4.0 + act_bytes(f)), s);
     if (f->cfg.dtype == SJD_DTYPE_BF16) launch_layernorm<bf16>(x, g, b, (bf16 *)y, rows, W, s);
+    else if (f->cfg.dtype == SJD_DTYPE_F16) launch_layernorm<f16>(x, g, b, (f16 *)y, rows, W, s);
     else launch_layernorm<float>(x, g, b, (float *)y, rows, W, s);
+}
+
+// whole-sequence causal attention on the fused qkv buffer [n*T, 3W] -> o [n*T, W]
+template <typename AT>
+void attention_full(const void *qkv, void *o, int n, int T, int W, int H, hipStream_t s) {
+    const AT *q = (const AT *)qkv;
+    if constexpr (sizeof(AT) == 2) {
+        if (W / H == 64) { launch_flash_attention_h16<AT>(q, (AT *)o, n, T, H, s); return; }
+    }
+    launch_attention_rows<AT, AT>(q, 3 * W, q + W, q + 2 * W, 3 * W, (int64_t)T * 3 * W, (AT *)o, W, n, T, 0, H, W / H, s);
+}
+
+template <typename AT>
+void attention_step(sjd_flow *f, int l, int B, int t, hipStream_t s) {
+    const sjd_config &c = f->cfg;
+    const size_t layer_off = (size_t)l * c.max_batch * c.seq_len * c.width;
+    launch_decode_attention<AT>((const AT *)f->qkv, (AT *)f->kcache + layer_off, (AT *)f->vcache + layer_off,
+                                (AT *)f->o, B, c.seq_len, t, c.n_heads, c.width / c.n_heads, s);
 }
 
 // Whole-sequence conditioner pass on `n` samples listed in `active` (device, nullable = identity).
@@ -177,7 +202,6 @@ void conditioner_pass(sjd_flow *f, int j, const float *x, int n, const int32_t *
     const int T = c.seq_len, W = c.width, D = c.token_dim, H = c.n_heads, RW = c.mlp_ratio * c.width;
     const int M = n * T;
     const int rev = (c.reverse_mask >> j) & 1;
-    const bool bf = c.dtype == SJD_DTYPE_BF16;
     const BlockW &bw = f->block[j];
     {
         ProfScope ps(f, SJD_PROF_OTHER, 2.0 * M * (double)D * W, (double)M * W * 4, s);
@@ -190,17 +214,9 @@ void conditioner_pass(sjd_flow *f, int j, const float *x, int n, const int32_t *
         {
             const double ab = act_bytes(f);
             ProfScope ps(f, SJD_PROF_ATTENTION, 2.0 * n * (double)T * (T + 1) * W, (double)M * 4 * W * ab, s);
-            if (bf && W / H == 64) {
-                launch_flash_attention_bf16((const bf16 *)f->qkv, (bf16 *)f->o, n, T, H, s);
-            } else if (bf) {
-                const bf16 *q = (const bf16 *)f->qkv;
-                launch_attention_rows<bf16, bf16>(q, 3 * W, q + W, q + 2 * W, 3 * W, (int64_t)T * 3 * W, (bf16 *)f->o, W,
-                                                  n, T, 0, H, W / H, s);
-            } else {
-                const float *q = (const float *)f->qkv;
-                launch_attention_rows<float, float>(q, 3 * W, q + W, q + 2 * W, 3 * W, (int64_t)T * 3 * W,
-                                                    (float *)f->o, W, n, T, 0, H, W / H, s);
-            }
+            if (c.dtype == SJD_DTYPE_BF16) attention_full<bf16>(f->qkv, f->o, n, T, W, H, s);
+            else if (c.dtype == SJD_DTYPE_F16) attention_full<f16>(f->qkv, f->o, n, T, W, H, s);
+            else attention_full<float>(f->qkv, f->o, n, T, W, H, s);
         }
         project(f, SJD_PROF_GEMM, f->o, lw.w_o, lw.t_o, lw.b_o, f->h, M, W, W, EPI_BIAS_RESIDUAL, true, s);
         layernorm(f, f->h, lw.ln2_g, lw.ln2_b, f->a, M, s);
@@ -215,9 +231,8 @@ void conditioner_pass(sjd_flow *f, int j, const float *x, int n, const int32_t *
 // layers against the key/value cache; the head output parameterises position t+1.
 void decode_step(sjd_flow *f, int j, const float *z, float *x, int B, int t, hipStream_t s) {
     const sjd_config &c = f->cfg;
-    const int T = c.seq_len, W = c.width, D = c.token_dim, H = c.n_heads, RW = c.mlp_ratio * c.width;
+    const int T = c.seq_len, W = c.width, D = c.token_dim, RW = c.mlp_ratio * c.width;
     const int rev = (c.reverse_mask >> j) & 1;
-    const bool bf = c.dtype == SJD_DTYPE_BF16;
     const BlockW &bw = f->block[j];
     const size_t ab = act_bytes(f);
     {
@@ -229,16 +244,11 @@ void decode_step(sjd_flow *f, int j, const float *z, float *x, int B, int t, hip
         layernorm(f, f->h, lw.ln1_g, lw.ln1_b, f->a, B, s);
         project(f, SJD_PROF_DECODE_GEMM, f->a, lw.w_qkv, lw.t_qkv, lw.b_qkv, f->qkv, B, 3 * W, W, EPI_BIAS, false, s);
         {
-            const size_t layer_off = (size_t)l * c.max_batch * T * W * ab;
             ProfScope ps(f, SJD_PROF_DECODE_ATTN, 4.0 * B * (double)(t + 1) * W,
                          (double)B * (2.0 * (t + 1) * W + 4.0 * W) * ab, s);
-            if (bf)
-                launch_decode_attention<bf16>((const bf16 *)f->qkv, (bf16 *)((char *)f->kcache + layer_off),
-                                              (bf16 *)((char *)f->vcache + layer_off), (bf16 *)f->o, B, T, t, H, W / H, s);
-            else
-                launch_decode_attention<float>((const float *)f->qkv, (float *)((char *)f->kcache + layer_off),
-                                               (float *)((char *)f->vcache + layer_off), (float *)f->o, B, T, t, H,
-                                               W / H, s);
+            if (c.dtype == SJD_DTYPE_BF16) attention_step<bf16>(f, l, B, t, s);
+            else if (c.dtype == SJD_DTYPE_F16) attention_step<f16>(f, l, B, t, s);
+            else attention_step<float>(f, l, B, t, s);
         }
         project(f, SJD_PROF_DECODE_GEMM, f->o, lw.w_o, lw.t_o, lw.b_o, f->h, B, W, W, EPI_BIAS_RESIDUAL, true, s);
         layernorm(f, f->h, lw.ln2_g, lw.ln2_b, f->a, B, s);
@@ -340,8 +350,9 @@ int sjd_flow_create(const sjd_config *cfg, sjd_flow **out) {
         c.max_batch < 1)
         return fail(SJD_EINVAL, "all sizes must be positive");
     if (c.width % c.n_heads) return fail(SJD_EINVAL, "width %d is not a multiple of n_heads %d", c.width, c.n_heads);
-    if (c.dtype != SJD_DTYPE_F32 && c.dtype != SJD_DTYPE_BF16) return fail(SJD_EINVAL, "unknown dtype %d", c.dtype);
-    if (c.dtype == SJD_DTYPE_BF16 && c.width % 64) return fail(SJD_EINVAL, "bf16 mode needs width %% 64 == 0");
+    if (c.dtype != SJD_DTYPE_F32 && c.dtype != SJD_DTYPE_BF16 && c.dtype != SJD_DTYPE_F16)
+        return fail(SJD_EINVAL, "unknown dtype %d", c.dtype);
+    if (c.dtype != SJD_DTYPE_F32 && c.width % 64) return fail(SJD_EINVAL, "16-bit modes need width %% 64 == 0");
     if (c.seq_len > 4096) return fail(SJD_EINVAL, "seq_len above 4096 is not supported");
     if (c.token_dim > 1024) return fail(SJD_EINVAL, "token_dim above 1024 is not supported");
     if ((double)c.max_batch * c.seq_len > 1.0e9) return fail(SJD_EINVAL, "max_batch * seq_len is too large");
@@ -364,7 +375,7 @@ int sjd_flow_create(const sjd_config *cfg, sjd_flow **out) {
     int rc = SJD_OK;
     auto A = [&](void **p, size_t n) { if (rc == SJD_OK) rc = dev_alloc(f, p, n); };
     A((void **)&f->blob, (size_t)c.n_blocks * block_floats(c) * sizeof(float));
-    if (c.dtype == SJD_DTYPE_BF16) A((void **)&f->arena, (size_t)c.n_blocks * arena_elems_per_block(c) * sizeof(bf16));
+    if (c.dtype != SJD_DTYPE_F32) A(&f->arena, (size_t)c.n_blocks * arena_elems_per_block(c) * 2);
     A((void **)&f->h, M * W * 4);
     A((void **)&f->p, M * 2 * D * 4);
     A(&f->a, M * W * ab);
@@ -413,15 +424,16 @@ int sjd_flow_load_weights(sjd_flow *f, const void *host_blob, size_t nbytes) {
     if (nbytes != want) return fail(SJD_EINVAL, "weight blob has %zu bytes, the configuration implies %zu", nbytes, want);
     HIP_TRY(hipMemcpy(f->blob, host_blob, nbytes, hipMemcpyHostToDevice));
     const size_t D = c.token_dim, W = c.width, T = c.seq_len, R = c.mlp_ratio;
-    const bool b16 = c.dtype == SJD_DTYPE_BF16;
+    const int dt = c.dtype;
     f->block.assign(c.n_blocks, BlockW());
-    bf16 *ar = f->arena;
-    auto prep = [&](const float *src, size_t K, size_t N) -> bf16 * {  // [K, N] float -> [N padded, K] bf16
-        if (!b16) return nullptr;
-        bf16 *dst = ar;
+    char *ar = (char *)f->arena;
+    auto prep = [&](const float *src, size_t K, size_t N) -> void * {  // [K, N] float -> [N padded, K] 16-bit
+        if (dt == SJD_DTYPE_F32) return nullptr;
+        void *dst = ar;
         const size_t rows = round_up(N, kNPad);
-        launch_transpose_to_bf16(src, dst, (int)K, (int)N, (int)K, (int)rows, 0);
-        ar += rows * K;
+        if (dt == SJD_DTYPE_BF16) launch_transpose_to_h16<bf16>(src, (bf16 *)dst, (int)K, (int)N, (int)K, (int)rows, 0);
+        else launch_transpose_to_h16<f16>(src, (f16 *)dst, (int)K, (int)N, (int)K, (int)rows, 0);
+        ar += rows * K * 2;
         return dst;
     };
     for (int j = 0; j < c.n_blocks; ++j) {
