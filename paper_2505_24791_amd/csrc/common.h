@@ -114,6 +114,33 @@ void launch_decode_attention(const AT *qkv, AT *kcache, AT *vcache, AT *o, int B
 template <typename HT>
 void launch_flash_attention_h16(const HT *qkv, HT *o, int n_samples, int T, int H, hipStream_t s);
 
+// Skinny 16-bit projection for single-token steps (M <= 256 rows, K % 32 == 0); same contract as
+// launch_gemm_h16.
+// frag: operands in the fragment-major layout of the 16x16x32 MFMA (A [M <= 64, K], Wt, and C unless
+// it is a float output without residual); requires M <= 64.  Otherwise everything is row-major.
+template <typename HT, typename OutT>
+void launch_skinny_gemm(const HT *A, const HT *Wt, const float *bias, const float *resid, OutT *C, int M, int N, int K,
+                        Epi epi, bool frag, hipStream_t s);
+
+// The same with LayerNorm of the float32 rows Hs [M, K] fused in front (gain g, shift be); returns
+// false (nothing launched) when the shape is outside what the fused kernel covers (M <= 64, K in
+// {256, 512, 768, 1024}).  Fragment-major operands only (Hs, Wt, and a 16-bit C).
+template <typename HT, typename OutT>
+bool launch_skinny_ln_gemm(const float *Hs, const float *g, const float *be, const HT *Wt, const float *bias, OutT *C,
+                           int M, int N, int K, Epi epi, hipStream_t s);
+
+// Single-token attention for head size 64 with the position read from device memory (*t_dev):
+// appends this step's k, v to the cache [B, T, W] and attends keys 0..t.
+template <typename HT>
+void launch_decode_attention_h16(const HT *qkv, HT *kcache, HT *vcache, HT *o, const int32_t *t_dev, int B, int T, int H,
+                                 bool frag, hipStream_t s);
+
+// Step boundary of the sequential inverse: x_{t+1} from the head row of position t (eq. 5), its
+// embedding into h, and t <- t+1 (device counter).  first != 0: x_0 = z_0, embedding of position 0, t <- 0.
+void launch_decode_advance(const float *p, const float *z, float *x, const float *w_in, const float *b_in,
+                           const float *pos, float *h, int32_t *t_dev, uint32_t *ticket, int B, int T, int D, int W,
+                           int reversed, int first, bool frag, hipStream_t s);
+
 // Jacobi epilogue.  p [n_rows, 2D] head output (row r of a sample parameterises position r+1).
 // For every listed sample that is still active: x <- z*exp(alpha)+mu in place, delta, pass count,
 // convergence flag.  Then the last workgroup rebuilds the active list.
@@ -144,5 +171,9 @@ void launch_split_params(const float *p, float *mu, float *alpha, int B, int T, 
 // Weight preparation on the device: dst[n, k] (16-bit, row length ldb, zero padded) = src[k, n] (float [K, N]).
 template <typename HT>
 void launch_transpose_to_h16(const float *src, HT *dst, int K, int N, int ldb, int n_rows_padded, hipStream_t s);
+
+// Weight preparation for the skinny kernels: fragment-major 16-bit copy of src [K, N] (see decode.hip).
+template <typename HT>
+void launch_weights_to_frag(const float *src, HT *dst, int K, int N, int n_rows_padded, hipStream_t s);
 
 }  // namespace sjd

@@ -246,4 +246,33 @@ void launch_transpose_to_h16(const float *src, HT *dst, int K, int N, int ldb, i
 template void launch_transpose_to_h16<bf16>(const float *, bf16 *, int, int, int, int, hipStream_t);
 template void launch_transpose_to_h16<f16>(const float *, f16 *, int, int, int, int, hipStream_t);
 
+// Fragment-major weight copy for the skinny kernels: dst holds, for column block nb = n/16 and
+// k-step ks = k/32, the 64 x 8 elements lane = 16*((k%32)/8) + n%16, e = k%8 contiguously
+// (dst[((nb*KS + ks)*64 + lane)*8 + e] = src[k, n]); columns up to n_rows_padded, zero filled.
+template <typename HT>
+__global__ __launch_bounds__(256) void weights_to_frag_kernel(const float *__restrict__ src, HT *__restrict__ dst, int K,
+                                                              int N, int n_rows_padded) {
+    const int KS = K / 32;
+    const size_t total = (size_t)n_rows_padded * K;
+    for (size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (size_t)gridDim.x * 256) {
+        const int e = idx & 7;
+        const int lane = (idx >> 3) & 63;
+        const size_t fr = idx >> 9;
+        const int ks = (int)(fr % KS), nb = (int)(fr / KS);
+        const int n = nb * 16 + (lane & 15);
+        const int k = ks * 32 + (lane >> 4) * 8 + e;
+        dst[idx] = from_f32<HT>(n < N ? src[(size_t)k * N + n] : 0.f);
+    }
+}
+
+template <typename HT>
+void launch_weights_to_frag(const float *src, HT *dst, int K, int N, int n_rows_padded, hipStream_t s) {
+    const size_t total = (size_t)n_rows_padded * K;
+    int grid = (int)((total + 255) / 256);
+    if (grid > 8192) grid = 8192;
+    hipLaunchKernelGGL(weights_to_frag_kernel<HT>, dim3(grid), dim3(256), 0, s, src, dst, K, N, n_rows_padded);
+}
+template void launch_weights_to_frag<bf16>(const float *, bf16 *, int, int, int, hipStream_t);
+template void launch_weights_to_frag<f16>(const float *, f16 *, int, int, int, hipStream_t);
+
 }  // namespace sjd

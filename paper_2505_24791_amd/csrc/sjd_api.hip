@@ -8,7 +8,9 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <map>
 #include <new>
+#include <tuple>
 #include <vector>
 
 #include "common.h"
@@ -38,10 +40,11 @@ struct LayerW {
     const float *ln1_g, *ln1_b, *b_qkv, *b_o, *ln2_g, *ln2_b, *b_fc1, *b_fc2;
     const float *w_qkv, *w_o, *w_fc1, *w_fc2;      // float32 [in, out] (views into the device blob)
     void *t_qkv, *t_o, *t_fc1, *t_fc2;             // 16-bit transposed [out (padded), in]
+    void *f_qkv, *f_o, *f_fc1, *f_fc2;             // 16-bit fragment-major copies for single-token steps
 };
 struct BlockW {
     const float *w_in, *b_in, *pos, *lnf_g, *lnf_b, *w_head, *b_head;
-    void *t_head;
+    void *t_head, *f_head;
     std::vector<LayerW> layer;
 };
 
@@ -57,6 +60,7 @@ struct sjd_flow {
     std::vector<void *> allocs;
     float *blob = nullptr;       // whole float32 blob on the device
     void *arena = nullptr;       // transposed 16-bit matrices
+    void *arena_frag = nullptr;  // the same matrices in fragment-major order (sequential fast path)
     std::vector<BlockW> block;
     // workspaces (element type depends on dtype: float or bf16 for a, qkv, o, f and the cache)
     float *h = nullptr, *p = nullptr;
@@ -66,6 +70,12 @@ struct sjd_flow {
     JacobiState st{};
     int32_t *active[2] = {nullptr, nullptr};
     int32_t *host_pin = nullptr;                // pinned: [0] n_active, [1] nonfinite, [2..] iters[B]
+    // sequential fast path: device step counter, ticket, capture stream, one graph per (block, batch)
+    int32_t *t_dev = nullptr;
+    uint32_t *ticket = nullptr;
+    hipStream_t cap_stream = nullptr;
+    std::map<std::tuple<int, int, const void *, const void *>, hipGraphExec_t> step_graphs;
+    int use_graphs = 1;
     hipEvent_t ev[SJD_MAX_BLOCKS + 1] = {};
     // profiling
     uint32_t prof_mask = 0;
@@ -324,10 +334,119 @@ int run_jacobi(sjd_flow *f, int j, const float *z, float *x, int batch, const sj
     return SJD_OK;
 }
 
+// ---- sequential fast path (16-bit modes, head size 64) ------------------------------------------
+bool fast_decode_ok(const sjd_flow *f) {
+    return f->cfg.dtype != SJD_DTYPE_F32 && f->cfg.width / f->cfg.n_heads == 64 && f->cfg.max_batch <= 256;
+}
+// Fragment-major operands: up to 64 rows and a width the fused LayerNorm projection covers.
+bool frag_ok(const sjd_flow *f, int batch) {
+    const int W = f->cfg.width;
+    return fast_decode_ok(f) && batch <= 64 && (W == 256 || W == 512 || W == 768 || W == 1024);
+}
+
+// Launches of one step (all layers, head, advance) for position *t_dev, on stream s.
+template <typename HT>
+void fast_step(sjd_flow *f, int j, const float *z, float *x, int B, bool frag, hipStream_t s) {
+    const sjd_config &c = f->cfg;
+    const int T = c.seq_len, W = c.width, D = c.token_dim, H = c.n_heads, RW = c.mlp_ratio * c.width;
+    const int rev = (c.reverse_mask >> j) & 1;
+    const BlockW &bw = f->block[j];
+    HT *a = (HT *)f->a, *qkv = (HT *)f->qkv, *o = (HT *)f->o, *ff = (HT *)f->f;
+    const double wb = 2.0;
+    auto gemm_bytes = [&](int N, int K, double outb) { return (double)K * N * wb + (double)B * K * wb + (double)B * N * outb; };
+    // LayerNorm + projection: fused when the operands are fragment-major, else two launches
+    auto ln_project = [&](const float *g, const float *be, const void *wt, const void *wf, const float *bias, void *out,
+                          int N, Epi epi, bool out_f32) {
+        ProfScope ps(f, SJD_PROF_DECODE_GEMM, 2.0 * B * (double)N * W, gemm_bytes(N, W, out_f32 ? 4 : 2), s);
+        if (frag) {
+            bool ok = out_f32 ? launch_skinny_ln_gemm<HT, float>(f->h, g, be, (const HT *)wf, bias, (float *)out, B, N, W, epi, s)
+                              : launch_skinny_ln_gemm<HT, HT>(f->h, g, be, (const HT *)wf, bias, (HT *)out, B, N, W, epi, s);
+            (void)ok;  // frag_ok() admits only widths the fused kernel covers
+        } else {
+            launch_layernorm<HT>(f->h, g, be, a, B, W, s);
+            if (out_f32) launch_skinny_gemm<HT, float>(a, (const HT *)wt, bias, nullptr, (float *)out, B, N, W, epi, false, s);
+            else launch_skinny_gemm<HT, HT>(a, (const HT *)wt, bias, nullptr, (HT *)out, B, N, W, epi, false, s);
+        }
+    };
+    for (int l = 0; l < c.n_layers; ++l) {
+        const LayerW &lw = bw.layer[l];
+        const size_t layer_off = (size_t)l * c.max_batch * T * W;
+        ln_project(lw.ln1_g, lw.ln1_b, lw.t_qkv, lw.f_qkv, lw.b_qkv, qkv, 3 * W, EPI_BIAS, false);
+        {
+            // mean prefix length T/2: keys and values read once
+            ProfScope ps(f, SJD_PROF_DECODE_ATTN, 4.0 * B * (T / 2.0) * W, (double)B * (T / 2.0) * W * 2 * wb, s);
+            launch_decode_attention_h16<HT>(qkv, (HT *)f->kcache + layer_off, (HT *)f->vcache + layer_off, o, f->t_dev, B,
+                                            T, H, frag, s);
+        }
+        {
+            ProfScope ps(f, SJD_PROF_DECODE_GEMM, 2.0 * B * (double)W * W, gemm_bytes(W, W, 8), s);
+            launch_skinny_gemm<HT, float>(o, (const HT *)(frag ? lw.f_o : lw.t_o), lw.b_o, f->h, f->h, B, W, W,
+                                          EPI_BIAS_RESIDUAL, frag, s);
+        }
+        ln_project(lw.ln2_g, lw.ln2_b, lw.t_fc1, lw.f_fc1, lw.b_fc1, ff, RW, EPI_BIAS_GELU, false);
+        {
+            ProfScope ps(f, SJD_PROF_DECODE_GEMM, 2.0 * B * (double)RW * W, gemm_bytes(W, RW, 8), s);
+            launch_skinny_gemm<HT, float>(ff, (const HT *)(frag ? lw.f_fc2 : lw.t_fc2), lw.b_fc2, f->h, f->h, B, W, RW,
+                                          EPI_BIAS_RESIDUAL, frag, s);
+        }
+    }
+    ln_project(bw.lnf_g, bw.lnf_b, bw.t_head, bw.f_head, bw.b_head, f->p, 2 * D, EPI_BIAS, true);
+    {
+        ProfScope ps(f, SJD_PROF_EPILOGUE, 0.0, (double)B * (D * 16.0 + W * 4.0), s);
+        launch_decode_advance(f->p, z, x, bw.w_in, bw.b_in, bw.pos, f->h, f->t_dev, f->ticket, B, T, D, W, rev, 0, frag, s);
+    }
+}
+
+void fast_step_any(sjd_flow *f, int j, const float *z, float *x, int B, bool frag, hipStream_t s) {
+    if (f->cfg.dtype == SJD_DTYPE_BF16) fast_step<bf16>(f, j, z, x, B, frag, s);
+    else fast_step<f16>(f, j, z, x, B, frag, s);
+}
+
+int run_sequential_fast(sjd_flow *f, int j, const float *z, float *x, int batch, hipStream_t s) {
+    const sjd_config &c = f->cfg;
+    const int T = c.seq_len, D = c.token_dim, W = c.width;
+    const int rev = (c.reverse_mask >> j) & 1;
+    const BlockW &bw = f->block[j];
+    const bool frag = frag_ok(f, batch);
+    launch_decode_advance(f->p, z, x, bw.w_in, bw.b_in, bw.pos, f->h, f->t_dev, f->ticket, batch, T, D, W, rev, 1, frag, s);
+    if (T == 1) return SJD_OK;
+    const bool eager = f->prof_mask != 0 || !f->use_graphs;
+    if (eager) {
+        for (int t = 0; t + 1 < T; ++t) fast_step_any(f, j, z, x, batch, frag, s);
+        HIP_TRY(hipGetLastError());
+        return SJD_OK;
+    }
+    hipGraphExec_t exec = nullptr;
+    // a captured step holds z and x as kernel arguments, so they are part of the key
+    auto key = std::make_tuple(j, batch, (const void *)z, (const void *)x);
+    auto it = f->step_graphs.find(key);
+    if (it != f->step_graphs.end()) {
+        exec = it->second;
+    } else {
+        // captured on the handle's own stream: the caller's may be the legacy default stream, which
+        // cannot be captured
+        if (f->step_graphs.size() >= 64) {
+            for (auto &kv : f->step_graphs) (void)hipGraphExecDestroy(kv.second);
+            f->step_graphs.clear();
+        }
+        hipGraph_t graph = nullptr;
+        HIP_TRY(hipStreamBeginCapture(f->cap_stream, hipStreamCaptureModeThreadLocal));
+        fast_step_any(f, j, z, x, batch, frag, f->cap_stream);
+        HIP_TRY(hipStreamEndCapture(f->cap_stream, &graph));
+        hipError_t e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+        (void)hipGraphDestroy(graph);
+        if (e != hipSuccess) return fail(SJD_EHIP, "hipGraphInstantiate failed: %s", hipGetErrorString(e));
+        f->step_graphs[key] = exec;
+    }
+    for (int t = 0; t + 1 < T; ++t) HIP_TRY(hipGraphLaunch(exec, s));
+    return SJD_OK;
+}
+
 int run_sequential(sjd_flow *f, int j, const float *z, float *x, int batch, hipStream_t s) {
     const int T = f->cfg.seq_len, D = f->cfg.token_dim;
     const int rev = (f->cfg.reverse_mask >> j) & 1;
     if (batch == 0) return SJD_OK;
+    if (fast_decode_ok(f)) return run_sequential_fast(f, j, z, x, batch, s);
     launch_decode_epilogue(f->p, z, x, batch, T, D, -1, rev, s);  // x_1 = y_1
     for (int t = 0; t + 1 < T; ++t) decode_step(f, j, z, x, batch, t, s);
     HIP_TRY(hipGetLastError());
@@ -371,11 +490,12 @@ int sjd_flow_create(const sjd_config *cfg, sjd_flow **out) {
     f->cfg = c;
     f->device = dev;
     const size_t T = c.seq_len, W = c.width, D = c.token_dim, R = c.mlp_ratio, B = c.max_batch, N = c.n_layers;
-    const size_t M = B * T, ab = act_bytes(f);
+    const size_t M = B * T > 64 ? B * T : 64, ab = act_bytes(f);  // single-token kernels work on 64-row tiles
     int rc = SJD_OK;
     auto A = [&](void **p, size_t n) { if (rc == SJD_OK) rc = dev_alloc(f, p, n); };
     A((void **)&f->blob, (size_t)c.n_blocks * block_floats(c) * sizeof(float));
     if (c.dtype != SJD_DTYPE_F32) A(&f->arena, (size_t)c.n_blocks * arena_elems_per_block(c) * 2);
+    if (fast_decode_ok(f)) A(&f->arena_frag, (size_t)c.n_blocks * arena_elems_per_block(c) * 2);
     A((void **)&f->h, M * W * 4);
     A((void **)&f->p, M * 2 * D * 4);
     A(&f->a, M * W * ab);
@@ -394,6 +514,11 @@ int sjd_flow_create(const sjd_config *cfg, sjd_flow **out) {
     A((void **)&f->active[0], B * 4);
     A((void **)&f->active[1], B * 4);
     f->st.ticket = nullptr;
+    A((void **)&f->t_dev, 4);
+    A((void **)&f->ticket, 4);
+    if (rc == SJD_OK && hipMemset(f->ticket, 0, 4) != hipSuccess) rc = fail(SJD_EHIP, "hipMemset failed");
+    if (rc == SJD_OK && hipStreamCreateWithFlags(&f->cap_stream, hipStreamNonBlocking) != hipSuccess)
+        rc = fail(SJD_EHIP, "hipStreamCreate failed");
     if (rc == SJD_OK && hipHostMalloc((void **)&f->host_pin, (B + 2) * sizeof(int32_t)) != hipSuccess)
         rc = fail(SJD_ENOMEM, "pinned host allocation failed");
     for (int i = 0; rc == SJD_OK && i <= c.n_blocks; ++i)
@@ -406,6 +531,8 @@ int sjd_flow_create(const sjd_config *cfg, sjd_flow **out) {
 void sjd_flow_destroy(sjd_flow *f) {
     if (!f) return;
     (void)hipDeviceSynchronize();
+    for (auto &kv : f->step_graphs) (void)hipGraphExecDestroy(kv.second);
+    if (f->cap_stream) (void)hipStreamDestroy(f->cap_stream);
     for (void *p : f->allocs) (void)hipFree(p);
     if (f->host_pin) (void)hipHostFree(f->host_pin);
     for (auto &e : f->ev) if (e) (void)hipEventDestroy(e);
@@ -436,6 +563,16 @@ int sjd_flow_load_weights(sjd_flow *f, const void *host_blob, size_t nbytes) {
         ar += rows * K * 2;
         return dst;
     };
+    char *arf = (char *)f->arena_frag;
+    auto prep_frag = [&](const float *src, size_t K, size_t N) -> void * {  // fragment-major 16-bit copy
+        if (!f->arena_frag) return nullptr;
+        void *dst = arf;
+        const size_t rows = round_up(N, kNPad);
+        if (dt == SJD_DTYPE_BF16) launch_weights_to_frag<bf16>(src, (bf16 *)dst, (int)K, (int)N, (int)rows, 0);
+        else launch_weights_to_frag<f16>(src, (f16 *)dst, (int)K, (int)N, (int)rows, 0);
+        arf += rows * K * 2;
+        return dst;
+    };
     for (int j = 0; j < c.n_blocks; ++j) {
         const float *p = f->blob + (size_t)j * bf;
         BlockW &bw = f->block[j];
@@ -461,12 +598,17 @@ int sjd_flow_load_weights(sjd_flow *f, const void *host_blob, size_t nbytes) {
             lw.t_o = prep(lw.w_o, W, W);
             lw.t_fc1 = prep(lw.w_fc1, W, R * W);
             lw.t_fc2 = prep(lw.w_fc2, R * W, W);
+            lw.f_qkv = prep_frag(lw.w_qkv, W, 3 * W);
+            lw.f_o = prep_frag(lw.w_o, W, W);
+            lw.f_fc1 = prep_frag(lw.w_fc1, W, R * W);
+            lw.f_fc2 = prep_frag(lw.w_fc2, R * W, W);
         }
         bw.lnf_g = p; p += W;
         bw.lnf_b = p; p += W;
         bw.w_head = p; p += W * 2 * D;
         bw.b_head = p;
         bw.t_head = prep(bw.w_head, W, 2 * D);
+        bw.f_head = prep_frag(bw.w_head, W, 2 * D);
     }
     HIP_TRY(hipDeviceSynchronize());
     HIP_TRY(hipGetLastError());

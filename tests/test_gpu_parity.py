@@ -138,6 +138,12 @@ BF16_CASES = [
     # T = 200: two 128-row query tiles with a ragged tail, four 64-key tiles; M = 5*200 = 1000 rows
     ("bf16_ragged", wl.FlowConfig("bf16_ragged", n_blocks=3, n_layers=2, width=128, n_heads=2, seq_len=200,
                                   token_dim=12, batch=5, bf16=True), True),
+    # width 256, 40 samples: single-token steps on fragment-major operands, 64-row tiles (3 row blocks live)
+    ("bf16_frag64", wl.FlowConfig("bf16_frag64", n_blocks=2, n_layers=2, width=256, n_heads=4, seq_len=40,
+                                  token_dim=8, batch=40, bf16=True), True),
+    # the same with at most 32 rows (two row blocks, 16 waves splitting K)
+    ("bf16_frag32", wl.FlowConfig("bf16_frag32", n_blocks=2, n_layers=1, width=256, n_heads=4, seq_len=24,
+                                  token_dim=8, batch=19, bf16=True), True),
     # head size 32: the generic attention path
     ("bf16_dh32", wl.FlowConfig("bf16_dh32", n_blocks=2, n_layers=1, width=64, n_heads=2, seq_len=50, token_dim=6,
                                 batch=3, bf16=True), True),
