@@ -153,7 +153,7 @@ __global__ __launch_bounds__(64 * NW) void skinny_gemm_kernel(const HT *__restri
             const int row = (mb0 + i) * 16 + 4 * kg + v;
             if (row >= M) continue;
             float val = t[v] + bv[q];
-            if (EPI == EPI_BIAS_GELU) val = gelu_erf(val);
+            if (EPI == EPI_BIAS_GELU) val = gelu_erf_h16(val);
             if (EPI == EPI_BIAS_RESIDUAL) val += rv[q * 4 + v];
             const size_t co = OUT_FRAG ? frag_off(row, col, KSN) : (size_t)row * N + col;
             C[co] = from_f32<OutT>(val);
@@ -287,7 +287,7 @@ __global__ __launch_bounds__(64 * NW) void skinny_ln_gemm_kernel(const float *__
             const int row = i * 16 + 4 * kg + v;
             if (row >= M) continue;
             float val = t[v] + bv;
-            if (EPI == EPI_BIAS_GELU) val = gelu_erf(val);
+            if (EPI == EPI_BIAS_GELU) val = gelu_erf_h16(val);
             const size_t co = OUT_FRAG ? frag_off(row, col, KSN) : (size_t)row * N + col;
             C[co] = from_f32<OutT>(val);
         }
