@@ -97,7 +97,9 @@ def main() -> int:
     d = prof[dominant]
     launches = max(d["launches"], 1)
     avg_s = d["ms"] * 1e-3 / launches
-    if dominant in ("gemm", "attention", "decode_gemm"):
+    # whole-sequence projections and attention are dense contractions (matrix-core bound); single-token
+    # steps stream weights and the KV prefix for a handful of rows (memory bound, in practice latency bound)
+    if dominant in ("gemm", "attention"):
         peak = PEAK_BF16_TFLOPS if cfg.bf16 else PEAK_F32_TFLOPS
         achieved = d["flops"] / launches / avg_s / 1e12
         roof = {"bound": "mfma" if cfg.bf16 else "alu", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
