@@ -3,8 +3,8 @@
 // Both operands are K-contiguous (the weights are stored transposed at load time), which is the
 // shape v_mfma_f32_32x32x16_{bf16,f16} wants: every lane feeds 8 consecutive k of one row.  A workgroup
 // of four waves (2 x 2) owns a BM x BN tile; a wave owns (BM/2) x (BN/2) as 32x32 MFMA blocks.
-// K is walked in index order in steps of 64 through LDS (rows padded by 16 bytes against bank
-// conflicts), the next step's global loads being in flight while the current one is multiplied.
+// K is walked in index order through LDS.  Two main loops: one stages tiles through registers into
+// two padded LDS buffers; the other fills four LDS stages with LDS-direct loads (see below).
 // No split-K and no atomics: an output row depends only on its own row of A, so results are
 // independent of which other rows share the tile or the batch.
 #include "common.h"
@@ -20,6 +20,73 @@ __device__ __forceinline__ int xcd_tile(int wg, int n_tiles) {
     const int per = (n_tiles + 7) >> 3;
     const int t = (wg & 7) * per + (wg >> 3);
     return t;
+}
+
+// Epilogue through LDS.  In the accumulators a lane owns one column and sixteen rows of each
+// 32x32 block (register v of lane (l32, g) is row 8*(v/4) + 4*g + v%4, column l32), which would
+// mean one 4-byte access per element.  Each wave therefore parks 32 rows of its sub-tile at a
+// time in its own slice of the (now idle) staging memory and takes them back row-wise, four
+// consecutive columns per lane, so that bias, GELU, the float32 residual read-modify-write and
+// the store all move 8 or 16 bytes per lane in runs of whole rows.  (row0, col0): first row and
+// column of the wave's sub-tile.  The caller has synchronised the workgroup after its last use of LDS.
+template <typename HT, int MI, int NI, int BN, typename OutT, int EPI>
+__device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[MI][NI], unsigned char *smem_raw,
+                                              const float *__restrict__ bias, const float *resid, OutT *C, int M, int N,
+                                              int row0, int col0, int lane, int wave) {
+    const int l32 = lane & 31, g = lane >> 5;
+    constexpr int WN = BN / 2;                 // columns of a wave's sub-tile
+    constexpr int EP = WN + 4;                 // LDS row pitch in floats
+    constexpr int LPR = WN / 4;                // lanes per row when reading back
+    constexpr int RPI = 64 / LPR;              // rows per read instruction
+    float *ep = reinterpret_cast<float *>(smem_raw) + wave * 32 * EP;
+    const int rl = lane / LPR, cl = (lane % LPR) * 4;
+    const int colg = col0 + cl;                // first of this lane's four columns
+    f32x4 bv4 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) bv4[e] = (colg + e < N) ? bias[colg + e] : 0.f;
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) ep[(8 * (v >> 2) + 4 * g + (v & 3)) * EP + 32 * j + l32] = acc[i][j][v];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int rr = 0; rr < 32; rr += RPI) {
+            const int rloc = rr + rl;
+            const int row = row0 + 32 * i + rloc;
+            f32x4 val = *reinterpret_cast<const f32x4 *>(&ep[rloc * EP + cl]);
+            if (row < M && colg < N) {
+                val += bv4;
+                if (EPI == EPI_BIAS_GELU) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) val[e] = gelu_erf_h16(val[e]);
+                }
+                OutT *dst = C + (size_t)row * N + colg;
+                if (colg + 3 < N && (N & 3) == 0) {
+                    if constexpr (sizeof(OutT) == 4) {
+                        if (EPI == EPI_BIAS_RESIDUAL) val += *reinterpret_cast<const f32x4 *>(resid + (size_t)row * N + colg);
+                        *reinterpret_cast<f32x4 *>(dst) = val;
+                    } else {
+                        typename Half16<HT>::v4 o4;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) o4[e] = from_f32<HT>(val[e]);
+                        *reinterpret_cast<typename Half16<HT>::v4 *>(dst) = o4;
+                    }
+                } else {  // ragged right edge, or rows not 16-byte aligned
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (colg + e < N) {
+                            float t = val[e];
+                            if (EPI == EPI_BIAS_RESIDUAL) t += resid[(size_t)row * N + colg + e];
+                            dst[e] = from_f32<OutT>(t);
+                        }
+                }
+            }
+        }
+    }
 }
 
 template <typename HT, int BM, int BN, int BK, int WGS_PER_CU, typename OutT, int EPI>
@@ -103,97 +170,158 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void gemm_h16_kernel(const HT *__r
         if (kt + 1 < KT) store_tile(cur ^ 1);
         if (kt + 2 < KT) load_tile(kt + 2);
         const HT *As = smem + cur * STAGE, *Bs = As + BM * G_LDS_STRIDE;
-        // operand fragments are double-buffered in registers: the reads of sub-step ks+1 are issued
-        // before the matrix instructions of sub-step ks and interleaved with them
-        v8 fa[2][MI], fb[2][NI];
-        auto read_frags = [&](int ks, int buf) {
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
-                fa[buf][i] = *reinterpret_cast<const v8 *>(&As[(wm0 + 32 * i + l32) * G_LDS_STRIDE + ks * 16 + 8 * g]);
-#pragma unroll
-            for (int j = 0; j < NI; ++j)
-                fb[buf][j] = *reinterpret_cast<const v8 *>(&Bs[(wn0 + 32 * j + l32) * G_LDS_STRIDE + ks * 16 + 8 * g]);
-        };
-        read_frags(0, 0);
 #pragma unroll
         for (int ks = 0; ks < KSUB; ++ks) {
-            const int b = ks & 1;
-            if (ks + 1 < KSUB) read_frags(ks + 1, b ^ 1);
+            v8 fa[MI], fb[NI];
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+                fa[i] = *reinterpret_cast<const v8 *>(&As[(wm0 + 32 * i + l32) * G_LDS_STRIDE + ks * 16 + 8 * g]);
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+                fb[j] = *reinterpret_cast<const v8 *>(&Bs[(wn0 + 32 * j + l32) * G_LDS_STRIDE + ks * 16 + 8 * g]);
 #pragma unroll
             for (int i = 0; i < MI; ++i)
 #pragma unroll
-                for (int j = 0; j < NI; ++j) acc[i][j] = Half16<HT>::mfma(fa[b][i], fb[b][j], acc[i][j]);
-            if (ks + 1 < KSUB) {
-                // one LDS read, then its share of the matrix instructions
-#pragma unroll
-                for (int q = 0; q < MI + NI; ++q) {
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x008, (MI * NI) / (MI + NI), 0);
-                }
-            }
+                for (int j = 0; j < NI; ++j) acc[i][j] = Half16<HT>::mfma(fa[i], fb[j], acc[i][j]);
         }
         __syncthreads();
     }
 
-    // Epilogue through LDS.  In the accumulators a lane owns one column and sixteen rows of each
-    // 32x32 block (register v of lane (l32, g) is row 8*(v/4) + 4*g + v%4, column l32), which would
-    // mean one 4-byte access per element.  Each wave therefore parks 32 rows of its sub-tile at a
-    // time in its own slice of the (now idle) staging memory and takes them back row-wise, four
-    // consecutive columns per lane, so that bias, GELU, the float32 residual read-modify-write and
-    // the store all move 8 or 16 bytes per lane in runs of whole rows.
-    constexpr int WN = BN / 2;                 // columns of a wave's sub-tile
-    constexpr int EP = WN + 4;                 // LDS row pitch in floats
-    constexpr int LPR = WN / 4;                // lanes per row when reading back
-    constexpr int RPI = 64 / LPR;              // rows per read instruction
-    float *ep = reinterpret_cast<float *>(smem_raw) + wave * 32 * EP;
-    const int rl = lane / LPR, cl = (lane % LPR) * 4;
-    const int colg = n0 + wn0 + cl;            // first of this lane's four columns
-    f32x4 bv4 = {0.f, 0.f, 0.f, 0.f};
+    tile_epilogue<HT, MI, NI, BN, OutT, EPI>(acc, smem_raw, bias, resid, C, M, N, m0 + wm0, n0 + wn0, lane, wave);
+}
+
+// ------------------------------------------------------------------------------------------------
+// 256x256 tile, k-tiles of 32, four LDS stages filled by LDS-direct global loads
+// (global_load_lds_dwordx4: no staging registers, no LDS write instructions).  A 1 KB load of a
+// wave covers 16 rows x 64 bytes (lane 4r + c fetches a 16-byte chunk of row r) and lands in LDS in
+// lane order.  Which chunk a lane fetches is swizzled, chunk = c ^ ((r >> 1) & 3), so that the
+// 16-byte fragment reads of the 32x32x16 MFMA (lane l32 + 32 g wants row l32, chunk 2 ks + g) fall
+// on all LDS banks.  Loads run three k-tiles ahead of the matrix instructions.  The compiler does
+// not see the dependence between an LDS-direct load and a later LDS read, so the waits are written
+// out: before the barrier that publishes tile kt+1 each wave waits until at most the 16 loads of
+// tiles kt+2 and kt+3 are outstanding.  Every matrix instruction is a slot, with the LDS reads and
+// global loads pinned between the slots.
+#define SJD_GPTR(p) ((const __attribute__((address_space(1))) void *)(p))
+#define SJD_LPTR(p) ((__attribute__((address_space(3))) void *)(p))
+
+template <typename HT, typename OutT, int EPI>
+__global__ __launch_bounds__(256, 1) void gemm_h16_dma_kernel(const HT *__restrict__ A, const HT *__restrict__ Bt,
+                                                              const float *__restrict__ bias, const float *resid,
+                                                              OutT *C, int M, int N, int K, int tiles_n, int n_tiles) {
+    typedef typename Half16<HT>::v8 v8;
+    constexpr int BM = 256, BN = 256, BK = 32, NST = 4;
+    constexpr int MI = 4, NI = 4;
+    constexpr int OPB = 16 * 1024;            // bytes of one operand in one stage: 8 row blocks x 2 k-steps x 1 KB
+    constexpr int STB = 2 * OPB;              // bytes per stage
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+
+    const int tile = xcd_tile(blockIdx.x, n_tiles);
+    if (tile >= n_tiles) return;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, g = lane >> 5;
+    const int tm = tile / tiles_n, tn = tile - tm * tiles_n;
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    f32x16 acc[MI][NI];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) bv4[e] = (colg + e < N) ? bias[colg + e] : 0.f;
-#pragma unroll
-    for (int i = 0; i < MI; ++i) {
-        __builtin_amdgcn_wave_barrier();
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < NI; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) ep[(8 * (v >> 2) + 4 * g + (v & 3)) * EP + 32 * j + l32] = acc[i][j][v];
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    // This wave loads, per k-tile, the 16-row blocks 4 wave + i (i = 0..3) of A and of B.
+    const int lr = lane >> 2, lc = (lane & 3) ^ ((lr >> 1) & 3);   // row within the block, chunk fetched
+    uint32_t a_eoff[4];
 #pragma unroll
-        for (int rr = 0; rr < 32; rr += RPI) {
-            const int rloc = rr + rl;
-            const int row = m0 + wm0 + 32 * i + rloc;
-            f32x4 val = *reinterpret_cast<const f32x4 *>(&ep[rloc * EP + cl]);
-            if (row < M && colg < N) {
-                val += bv4;
-                if (EPI == EPI_BIAS_GELU) {
+    for (int i = 0; i < 4; ++i) {
+        int row = m0 + (wave * 4 + i) * 16 + lr;
+        row = row < M ? row : M - 1;                       // rows past the end: re-read the last row, never stored
+        a_eoff[i] = (uint32_t)row * (uint32_t)K + (uint32_t)(lc * 8);
+    }
+    const uint32_t b_eoff = (uint32_t)(n0 + wave * 64 + lr) * (uint32_t)K + (uint32_t)(lc * 8);
+    const size_t b_istep = (size_t)16 * K;                  // Bt rows are padded to the tile: no clamp
+    const int KT = K / BK;
+    auto issue_loads = [&](int kt_, int first, int count) {  // blocks first .. first+count-1 of the wave's eight
+        const int ktc = kt_ < KT ? kt_ : KT - 1;             // past the end: reload the last tile into a dead stage
+        const HT *Ak = A + (size_t)ktc * BK;
+        const HT *Bk = Bt + (size_t)ktc * BK;
+        unsigned char *st = smem_raw + (kt_ % NST) * STB;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) val[e] = gelu_erf_h16(val[e]);
-                }
-                OutT *dst = C + (size_t)row * N + colg;
-                if (colg + 3 < N && (N & 3) == 0) {
-                    if constexpr (sizeof(OutT) == 4) {
-                        if (EPI == EPI_BIAS_RESIDUAL) val += *reinterpret_cast<const f32x4 *>(resid + (size_t)row * N + colg);
-                        *reinterpret_cast<f32x4 *>(dst) = val;
-                    } else {
-                        typename Half16<HT>::v4 o4;
+        for (int q = first; q < first + count; ++q) {
+            if (q < 4) {
+                __builtin_amdgcn_global_load_lds(SJD_GPTR(Ak + a_eoff[q]), SJD_LPTR(st + (wave * 4 + q) * 1024), 16, 0, 0);
+            } else {
+                const int i = q - 4;
+                __builtin_amdgcn_global_load_lds(SJD_GPTR(Bk + i * b_istep + b_eoff),
+                                                 SJD_LPTR(st + OPB + (wave * 4 + i) * 1024), 16, 0, 0);
+            }
+        }
+    };
+    v8 fa[2][MI], fb[2][NI];
+    // fragment (32 rows from row block r of the wave's sub-tile, k-step ks): row l32 is row l32 & 15 of
+    // 16-row block 2 r + (l32 >> 4); its chunk 2 ks + g sits in slot (2 ks + g) ^ swizzle(row)
+    const int rr = l32 & 15, swz = (rr >> 1) & 3;
+    const int frag_base = (l32 >> 4) * 1024 + rr * 64;
+    const int frag_k[2] = {frag_base + ((g ^ swz) << 4), frag_base + (((2 + g) ^ swz) << 4)};
+    auto read_one = [&](int stage, int ks, int buf, int r) {
+        const unsigned char *st = smem_raw + stage * STB + frag_k[ks];
+        if (r < MI) fa[buf][r] = *reinterpret_cast<const v8 *>(st + (wm * 8 + 2 * r) * 1024);
+        else fb[buf][r - MI] = *reinterpret_cast<const v8 *>(st + OPB + (wn * 8 + 2 * (r - MI)) * 1024);
+    };
+
+    issue_loads(0, 0, 8);
+    issue_loads(1, 0, 8);
+    issue_loads(2, 0, 8);
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (16 & 15) | ((16 >> 4) << 14));  // vmcnt(16): tile 0 has landed
+    __builtin_amdgcn_s_barrier();
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) o4[e] = from_f32<HT>(val[e]);
-                        *reinterpret_cast<typename Half16<HT>::v4 *>(dst) = o4;
+    for (int r = 0; r < 8; ++r) read_one(0, 0, 0, r);
+
+    for (int kt = 0; kt < KT; ++kt) {
+        const int cur = kt % NST, nxt = (kt + 1) % NST;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+            for (int m = 0; m < 16; ++m) {
+                if (ks == 0) {
+                    if ((m & 1) == 0) read_one(cur, 1, 1, m >> 1);            // fragments of the second k-step
+                    if ((m & 3) == 1) issue_loads(kt + 3, m >> 2, 1);          // A blocks of tile kt+3
+                } else {
+                    if (m < 8 && (m & 1) == 1) issue_loads(kt + 3, 4 + (m >> 1), 1);  // B blocks of tile kt+3
+                    if (m == 8) {
+                        // tile kt+1 complete (only tiles kt+2, kt+3 may be in flight), own LDS reads done
+                        __builtin_amdgcn_s_waitcnt((16 & 15) | ((16 >> 4) << 14) | (7 << 4) | (0 << 8));
+                        __builtin_amdgcn_s_barrier();
                     }
-                } else {  // ragged right edge, or rows not 16-byte aligned
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (colg + e < N) {
-                            float t = val[e];
-                            if (EPI == EPI_BIAS_RESIDUAL) t += resid[(size_t)row * N + colg + e];
-                            dst[e] = from_f32<OutT>(t);
-                        }
+                    if (m >= 8) read_one(nxt, 0, 0, m - 8);                    // first k-step of the next tile
                 }
+                acc[m / NI][m % NI] = Half16<HT>::mfma(fa[ks][m / NI], fb[ks][m % NI], acc[m / NI][m % NI]);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
     }
+    __builtin_amdgcn_s_waitcnt(0);  // every outstanding LDS-direct load has landed before LDS is reused
+    __syncthreads();
+    tile_epilogue<HT, MI, NI, BN, OutT, EPI>(acc, smem_raw, bias, resid, C, M, N, m0 + wm * 128, n0 + wn * 128, lane, wave);
+}
+
+template <typename HT, typename OutT, int EPI>
+static void launch_dma(const HT *A, const HT *Bt, const float *bias, const float *resid, OutT *C, int M, int N, int K,
+                       hipStream_t s) {
+    const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
+    const int n_tiles = tiles_m * tiles_n;
+    const int grid = ((n_tiles + 7) / 8) * 8;
+    const size_t smem = 4 * 32 * 1024;
+    auto kern = gemm_h16_dma_kernel<HT, OutT, EPI>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), smem, s, A, Bt, bias, resid, C, M, N, K, tiles_n, n_tiles);
 }
 
 template <typename HT, int BM, int BN, int BK, int WGS_PER_CU, typename OutT, int EPI>
@@ -214,15 +342,22 @@ static void launch_tile(const HT *A, const HT *Bt, const float *bias, const floa
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), smem, s, A, Bt, bias, resid, C, M, N, K, tiles_n, n_tiles);
 }
 
-// Tile choice.  256x128x32 with two workgroups per CU: one workgroup's epilogue and barrier stalls
-// hide behind the other's matrix instructions (measured 5-40 % faster than 256x256x64 with one
-// workgroup per CU on every projection of the workloads).  128x128 covers small problems.  Weight
-// matrices are padded to 256 rows, so tiles never read past a matrix.
+// Kernel choice, from measurements on the workloads' shapes (TFLOP/s, M = 32768):
+//   256x128x32 staged through registers, two workgroups per CU: one workgroup's epilogue and barrier
+//     stalls hide behind the other's matrix instructions - best when the epilogue is a large share
+//     (GELU: 648 vs 606; float32 residual with K = 1024: 610 vs 578) and for K <= 768;
+//   256x256x32 LDS-direct, one workgroup per CU: best main loop (K = 4096: 1025 vs 820) - used when
+//     the k-loop dominates.
+//   128x128x64 covers small problems.  Weight matrices are padded to 256 rows, so tiles never read
+//   past a matrix.
 template <typename HT, typename OutT, int EPI>
 static void pick_tile(const HT *A, const HT *Bt, const float *bias, const float *resid, OutT *C, int M, int N, int K,
                       hipStream_t s) {
     const long t128 = (long)((M + 127) / 128) * ((N + 127) / 128);
-    if (N >= 128 && M >= 256 && t128 >= 512) launch_tile<HT, 256, 128, 32, 2, OutT, EPI>(A, Bt, bias, resid, C, M, N, K, s);
+    const long t256 = (long)((M + 255) / 256) * ((N + 255) / 256);
+    const bool deep = K >= 3072 || (EPI == EPI_BIAS && K >= 1024 && N >= 1024);
+    if (deep && M >= 256 && N >= 256 && t256 >= 256) launch_dma<HT, OutT, EPI>(A, Bt, bias, resid, C, M, N, K, s);
+    else if (N >= 128 && M >= 256 && t128 >= 512) launch_tile<HT, 256, 128, 32, 2, OutT, EPI>(A, Bt, bias, resid, C, M, N, K, s);
     else launch_tile<HT, 128, 128, 64, 1, OutT, EPI>(A, Bt, bias, resid, C, M, N, K, s);
 }
 

@@ -117,12 +117,18 @@ def blob_floats(cfg: FlowConfig) -> int:
 
 
 def round_to_bf16(a: np.ndarray) -> np.ndarray:
-    """Round float32 values to the nearest bf16 (ties to even); result is float32 again."""
+    """Round float32 values to the nearest bf16 (ties to even); result is float32 again.
+    (Finite inputs far from overflow, which is all this module draws.)"""
     a = np.ascontiguousarray(a, dtype=np.float32)
-    u = a.view(np.uint32).astype(np.uint64)
-    lsb = (u >> 16) & 1
-    u = (u + 0x7FFF + lsb) & 0xFFFF0000
-    return u.astype(np.uint32).view(np.float32).reshape(a.shape)
+    out = np.empty_like(a)
+    flat_in, flat_out = a.reshape(-1), out.reshape(-1)
+    step = 1 << 24
+    for i in range(0, flat_in.size, step):          # chunked: no blob-sized temporaries
+        u = flat_in[i:i + step].view(np.uint32)
+        r = u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))
+        r &= np.uint32(0xFFFF0000)
+        flat_out[i:i + step] = r.view(np.float32)
+    return out
 
 
 def make_weights(cfg: FlowConfig, seed_base: int = WEIGHT_SEED_BASE, *, perturb_affine: bool = False,
@@ -151,6 +157,30 @@ def make_weights(cfg: FlowConfig, seed_base: int = WEIGHT_SEED_BASE, *, perturb_
     assert off == blob.size
     if cfg.bf16:
         blob = round_to_bf16(blob)
+    return blob
+
+
+def cached_weights(cfg: FlowConfig, cache_dir: str | None = None) -> np.ndarray:
+    """``make_weights(cfg)`` with an on-disk cache (``.npy`` under the system temp directory): the
+    larger workloads draw several hundred million numbers, which takes longer than the GPU work."""
+    import os
+    import tempfile
+    d = cache_dir or os.path.join(tempfile.gettempdir(), "sjd_workloads")
+    os.makedirs(d, exist_ok=True)
+    path = os.path.join(d, f"{cfg.name}_K{cfg.n_blocks}_N{cfg.n_layers}_W{cfg.width}_T{cfg.seq_len}_D{cfg.token_dim}"
+                           f"_{'bf16' if cfg.bf16 else 'f32'}_{WEIGHT_SEED_BASE}.npy")
+    if os.path.exists(path):
+        try:
+            blob = np.load(path)
+            if blob.dtype == np.float32 and blob.size == blob_floats(cfg):
+                return blob
+        except Exception:
+            pass
+    blob = make_weights(cfg)
+    try:
+        np.save(path, blob)
+    except OSError:
+        pass
     return blob
 
 
