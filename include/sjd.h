@@ -151,6 +151,17 @@ SJD_API int sjd_sample(sjd_flow *flow, const float *z_dev, float *x_dev, int bat
 SJD_API int sjd_conditioner(sjd_flow *flow, int block, const float *x_dev, float *mu_dev, float *alpha_dev, int batch,
                     void *hip_stream);
 
+/* One dense projection of the conditioner on its own, C = epi(A * W + bias), in a 16-bit mode: the
+ * building block of every whole-sequence pass (the s_k, g_k networks of eq. 5 are stacks of these),
+ * exported so that each matrix-core kernel can be checked against the oracle on small shapes.
+ * All pointers are DEVICE memory.  a_dev: [M, K] 16-bit row-major.  wt_dev: the weight TRANSPOSED,
+ * [N rounded up to a multiple of 256, K] 16-bit, K contiguous, padding rows zero.  bias_dev [N] float32.
+ * epilogue 0: c_dev [M, N] 16-bit = A W + bias;  1: c_dev = GELU(A W + bias) (erf form);
+ * 2: resid_out_dev [M, N] float32 += A W + bias (c_dev unused).  K must be a multiple of 64.
+ * kernel: 0 chosen by shape, 1..3 a specific tile kernel.  dtype: SJD_DTYPE_BF16 or SJD_DTYPE_F16. */
+SJD_API int sjd_op_linear_h16(int dtype, int kernel, const void *a_dev, const void *wt_dev, const float *bias_dev,
+                              float *resid_out_dev, void *c_dev, int M, int N, int K, int epilogue, void *hip_stream);
+
 /* Kernel-family timing: when enabled, every launch of the selected families (bit f of
  * family_mask = SJD_PROF_* f) is bracketed by events on the caller's stream.  Costs a little time per launch. */
 SJD_API int sjd_profile_enable(sjd_flow *flow, uint32_t family_mask);

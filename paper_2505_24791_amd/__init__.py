@@ -24,7 +24,7 @@ PROF_FAMILIES = 6
 PROF_NAMES = ("gemm", "attention", "epilogue", "decode_gemm", "decode_attn", "other")
 
 EXPORTS = ("sjd_flow_create", "sjd_flow_load_weights", "sjd_jacobi_inverse_block", "sjd_sequential_inverse_block",
-           "sjd_sample", "sjd_conditioner", "sjd_profile_enable", "sjd_profile_read", "sjd_flow_device_bytes",
+           "sjd_sample", "sjd_conditioner", "sjd_op_linear_h16", "sjd_profile_enable", "sjd_profile_read", "sjd_flow_device_bytes",
            "sjd_last_error", "sjd_flow_destroy")
 
 
@@ -73,6 +73,7 @@ def load_library() -> C.CDLL:
     lib.sjd_sequential_inverse_block.argtypes = [vp, C.c_int, fp, fp, C.c_int, vp]
     lib.sjd_sample.argtypes = [vp, fp, fp, C.c_int, C.c_uint32, C.POINTER(SjdJacobiOpts), C.POINTER(SjdStats), i32p, vp]
     lib.sjd_conditioner.argtypes = [vp, C.c_int, fp, fp, fp, C.c_int, vp]
+    lib.sjd_op_linear_h16.argtypes = [C.c_int, C.c_int, vp, vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, vp]
     lib.sjd_profile_enable.argtypes = [vp, C.c_uint32]
     lib.sjd_profile_read.argtypes = [vp, C.POINTER(SjdProfile), C.c_int]
     lib.sjd_flow_device_bytes.argtypes = [vp]
@@ -116,6 +117,25 @@ def _dev(t, shape=None) -> C.c_void_p:
     if shape is not None:
         assert tuple(t.shape) == tuple(shape), (tuple(t.shape), tuple(shape))
     return C.c_void_p(t.data_ptr())
+
+
+def op_linear_h16(a, wt, bias, M, N, K, epilogue, *, resid=None, kernel=0):
+    """``sjd_op_linear_h16`` on torch tensors: a [M,K] and wt [N_pad,K] in float16 or bfloat16 (same
+    type), bias [N] float32; returns c [M,N] (16-bit) or, for epilogue 2, updates ``resid`` in place."""
+    import torch
+    lib = load_library()
+    assert a.is_cuda and wt.is_cuda and a.dtype == wt.dtype and a.is_contiguous() and wt.is_contiguous()
+    assert wt.shape[0] % 256 == 0 and wt.shape[0] >= N and wt.shape[1] == K and tuple(a.shape) == (M, K)
+    dtype = DTYPE_F16 if a.dtype == torch.float16 else DTYPE_BF16
+    c = None
+    if epilogue == 2:
+        assert resid is not None and resid.dtype == torch.float32 and tuple(resid.shape) == (M, N) and resid.is_contiguous()
+    else:
+        c = torch.empty((M, N), dtype=a.dtype, device=a.device)
+    _check(lib.sjd_op_linear_h16(dtype, kernel, C.c_void_p(a.data_ptr()), C.c_void_p(wt.data_ptr()),
+                                 C.c_void_p(bias.data_ptr()), C.c_void_p(resid.data_ptr()) if resid is not None else None,
+                                 C.c_void_p(c.data_ptr()) if c is not None else None, M, N, K, epilogue, _stream_ptr()))
+    return resid if epilogue == 2 else c
 
 
 class Flow:

@@ -105,9 +105,11 @@ void launch_gemm_f32(const float *A, const float *B, const float *bias, const fl
 // 16-bit MFMA projection (HT = bf16 or f16): C[M,N] = epi(A[M,K] * Bt[N,K]^T + bias); Bt holds the
 // weight transposed, K contiguous, with at least round_up(N, 256) rows (zero filled).  K % 64 == 0.
 // OutT = HT (EPI_BIAS, EPI_BIAS_GELU) or float (EPI_BIAS, EPI_BIAS_RESIDUAL).
+// kernel: 0 = chosen by shape; 1 = 256x128x32 staged through registers; 2 = 256x256x64 LDS-direct;
+// 3 = 128x128x64 (the explicit choices exist so that each kernel can be checked on small shapes).
 template <typename HT, typename OutT>
 void launch_gemm_h16(const HT *A, const HT *Bt, const float *bias, const float *resid, OutT *C, int M, int N, int K,
-                     Epi epi, hipStream_t s);
+                     Epi epi, hipStream_t s, int kernel = 0);
 
 // Causal attention, one wave per (sample, head, query row); works for any shape and both types.
 // q rows: q + (sample*q_rows_per_sample + r) * q_stride; row r (processing position t0 + r) attends
@@ -131,13 +133,13 @@ void launch_flash_attention_h16(const HT *qkv, HT *o, int n_samples, int T, int 
 // Skinny 16-bit projection for single-token steps (M <= 256 rows, K % 32 == 0); same contract as
 // launch_gemm_h16.
 // frag: operands in the fragment-major layout of the 16x16x32 MFMA (A [M <= 64, K], Wt, and C unless
-// it is a float output without residual); requires M <= 64.  Otherwise everything is row-major.
+// it is a float output without residual).  Otherwise everything is row-major.
 template <typename HT, typename OutT>
 void launch_skinny_gemm(const HT *A, const HT *Wt, const float *bias, const float *resid, OutT *C, int M, int N, int K,
                         Epi epi, bool frag, hipStream_t s);
 
 // The same with LayerNorm of the float32 rows Hs [M, K] fused in front (gain g, shift be); returns
-// false (nothing launched) when the shape is outside what the fused kernel covers (M <= 64, K in
+// false (nothing launched) when the shape is outside what the fused kernel covers (K in
 // {256, 512, 768, 1024}).  Fragment-major operands only (Hs, Wt, and a 16-bit C).
 template <typename HT, typename OutT>
 bool launch_skinny_ln_gemm(const float *Hs, const float *g, const float *be, const HT *Wt, const float *bias, OutT *C,

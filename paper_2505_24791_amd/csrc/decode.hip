@@ -72,7 +72,7 @@ __global__ __launch_bounds__(64 * NW) void skinny_gemm_kernel(const HT *__restri
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = lane & 15, kg = lane >> 4;
     const int n0 = blockIdx.x * 16 * NB;
-    const int mb0 = SPLITK ? 0 : wave * MB;
+    const int mb0 = SPLITK ? (int)blockIdx.y * MB : wave * MB;  // SPLITK: blockIdx.y selects a group of 16*MB rows
     const int steps = K / 32;
     const int s_begin = SPLITK ? (wave * steps) / NW : 0;
     const int s_end = SPLITK ? ((wave + 1) * steps) / NW : steps;
@@ -182,6 +182,7 @@ __global__ __launch_bounds__(64 * NW) void skinny_ln_gemm_kernel(const float *__
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = lane & 15, kg = lane >> 4;
     const int n0 = blockIdx.x * 16;
+    const int mb0 = blockIdx.y * MB;        // blockIdx.y selects a group of 16*MB rows
     const int k0 = wave * 32 * S + kg * 8;  // this lane's first k; step s adds 32*s
     constexpr int KS = K / 32;
     constexpr bool OUT_FRAG = sizeof(OutT) == 2;
@@ -196,7 +197,7 @@ __global__ __launch_bounds__(64 * NW) void skinny_ln_gemm_kernel(const float *__
     for (int i = 0; i < MB; ++i) {
 #pragma unroll
         for (int s = 0; s < S; ++s) {
-            const float *hp = Hs + (((size_t)i * KS + wave * S + s) * 64 + lane) * 8;
+            const float *hp = Hs + (((size_t)(mb0 + i) * KS + wave * S + s) * 64 + lane) * 8;
             xr[i][s][0] = *reinterpret_cast<const f32x4 *>(hp);
             xr[i][s][1] = *reinterpret_cast<const f32x4 *>(hp + 4);
         }
@@ -284,7 +285,7 @@ __global__ __launch_bounds__(64 * NW) void skinny_ln_gemm_kernel(const float *__
         for (int w = 1; w < NW; ++w) t += red[(w * MB + i) * 64 + lane];
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            const int row = i * 16 + 4 * kg + v;
+            const int row = (mb0 + i) * 16 + 4 * kg + v;
             if (row >= M) continue;
             float val = t[v] + bv;
             if (EPI == EPI_BIAS_GELU) val = gelu_erf_h16(val);
@@ -297,8 +298,8 @@ __global__ __launch_bounds__(64 * NW) void skinny_ln_gemm_kernel(const float *__
 template <typename HT, int MB, int NW, int S, int EPI, typename OutT>
 static void launch_ln_cfg(const float *Hs, const float *g, const float *be, const HT *Wt, const float *bias, OutT *C,
                           int M, int N, hipStream_t s) {
-    hipLaunchKernelGGL((skinny_ln_gemm_kernel<HT, MB, NW, S, EPI, OutT>), dim3((N + 15) / 16), dim3(64 * NW), 0, s, Hs,
-                       g, be, Wt, bias, C, M, N);
+    hipLaunchKernelGGL((skinny_ln_gemm_kernel<HT, MB, NW, S, EPI, OutT>), dim3((N + 15) / 16, (M + 16 * MB - 1) / (16 * MB)),
+                       dim3(64 * NW), 0, s, Hs, g, be, Wt, bias, C, M, N);
 }
 
 template <typename HT, int EPI, typename OutT>
@@ -322,7 +323,6 @@ template <typename HT, typename OutT>
 bool launch_skinny_ln_gemm(const float *Hs, const float *g, const float *be, const HT *Wt, const float *bias, OutT *C,
                            int M, int N, int K, Epi epi, hipStream_t s) {
     if (M <= 0 || N <= 0) return true;
-    if (M > 64) return false;
     if constexpr (sizeof(OutT) == 4) {
         return launch_ln_epi<HT, EPI_BIAS, float>(Hs, g, be, Wt, bias, C, M, N, K, s);
     } else {
@@ -343,16 +343,17 @@ template <typename HT, int MB, int NB, int NW, bool SPLITK, bool FRAG, int EPI, 
 static void launch_skinny_cfg(const HT *A, const HT *Wt, const float *bias, const float *resid, OutT *C, int M, int N,
                               int K, hipStream_t s) {
     const int grid = (N + 16 * NB - 1) / (16 * NB);
-    hipLaunchKernelGGL((skinny_gemm_kernel<HT, MB, NB, NW, SPLITK, FRAG, EPI, OutT>), dim3(grid), dim3(64 * NW), 0, s, A,
-                       Wt, bias, resid, C, M, N, K);
+    const int groups = SPLITK ? (M + 16 * MB - 1) / (16 * MB) : 1;
+    hipLaunchKernelGGL((skinny_gemm_kernel<HT, MB, NB, NW, SPLITK, FRAG, EPI, OutT>), dim3(grid, groups), dim3(64 * NW), 0,
+                       s, A, Wt, bias, resid, C, M, N, K);
 }
 
 template <typename HT, int EPI, typename OutT>
 static void launch_skinny_epi(const HT *A, const HT *Wt, const float *bias, const float *resid, OutT *C, int M, int N,
                               int K, bool frag, hipStream_t s) {
-    // Up to 64 rows (fragment-major operands): one 16-column block per workgroup, K split over 8
-    // waves (16 for very few rows): every wave has a handful of loads and matrix instructions,
-    // which is what a launch of this size needs.  Above that (row-major operands): waves split the
+    // Fragment-major operands: a workgroup owns one 16-column block and a group of up to 64 rows, K
+    // split over 8 waves (16 for at most 32 rows): every wave has a handful of loads and matrix
+    // instructions, which is what a launch of this size needs.  Row-major operands: waves split the
     // rows and a workgroup owns 32 columns.
     if (frag) {
         if (M <= 32) launch_skinny_cfg<HT, 2, 1, 16, true, true, EPI, OutT>(A, Wt, bias, resid, C, M, N, K, s);

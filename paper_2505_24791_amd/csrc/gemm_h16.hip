@@ -191,16 +191,16 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void gemm_h16_kernel(const HT *__r
 }
 
 // ------------------------------------------------------------------------------------------------
-// 256x256 tile, k-tiles of 32, four LDS stages filled by LDS-direct global loads
+// 256x256 tile, k-tiles of 64, two LDS stages filled by LDS-direct global loads
 // (global_load_lds_dwordx4: no staging registers, no LDS write instructions).  A 1 KB load of a
-// wave covers 16 rows x 64 bytes (lane 4r + c fetches a 16-byte chunk of row r) and lands in LDS in
-// lane order.  Which chunk a lane fetches is swizzled, chunk = c ^ ((r >> 1) & 3), so that the
-// 16-byte fragment reads of the 32x32x16 MFMA (lane l32 + 32 g wants row l32, chunk 2 ks + g) fall
-// on all LDS banks.  Loads run three k-tiles ahead of the matrix instructions.  The compiler does
-// not see the dependence between an LDS-direct load and a later LDS read, so the waits are written
-// out: before the barrier that publishes tile kt+1 each wave waits until at most the 16 loads of
-// tiles kt+2 and kt+3 are outstanding.  Every matrix instruction is a slot, with the LDS reads and
-// global loads pinned between the slots.
+// wave covers 8 rows x 128 bytes - whole cache lines, which matters: at this tile size the kernel
+// moves (256+256)*2 bytes per 2*256*256 flops from L2, and half-used lines double that - and lands
+// in LDS in lane order (lane 8r + c holds a 16-byte chunk of row r).  Which chunk a lane fetches is
+// swizzled, chunk = c ^ r, so that the 16-byte fragment reads of the 32x32x16 MFMA (lane
+// l32 + 32 g wants row l32, chunk 2 ks + g) fall on all LDS banks.  The compiler does not see the
+// dependence between an LDS-direct load and a later LDS read, so the waits are written out: a
+// wave waits for its own loads of tile kt+1 before the barrier that publishes that tile.  Every
+// matrix instruction is a slot, with the LDS reads and global loads pinned between the slots.
 #define SJD_GPTR(p) ((const __attribute__((address_space(1))) void *)(p))
 #define SJD_LPTR(p) ((__attribute__((address_space(3))) void *)(p))
 
@@ -209,16 +209,17 @@ __global__ __launch_bounds__(256, 1) void gemm_h16_dma_kernel(const HT *__restri
                                                               const float *__restrict__ bias, const float *resid,
                                                               OutT *C, int M, int N, int K, int tiles_n, int n_tiles) {
     typedef typename Half16<HT>::v8 v8;
-    constexpr int BM = 256, BN = 256, BK = 32, NST = 4;
-    constexpr int MI = 4, NI = 4;
-    constexpr int OPB = 16 * 1024;            // bytes of one operand in one stage: 8 row blocks x 2 k-steps x 1 KB
+    constexpr int BM = 256, BN = 256, BK = 64;
+    constexpr int MI = 4, NI = 4, KSUB = BK / 16;
+    constexpr int OPB = 32 * 1024;            // bytes of one operand in one stage: 32 blocks of 8 rows x 128 B
     constexpr int STB = 2 * OPB;              // bytes per stage
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
 
     const int tile = xcd_tile(blockIdx.x, n_tiles);
     if (tile >= n_tiles) return;
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps LDS bases in scalar registers
     const int l32 = lane & 31, g = lane >> 5;
     const int tm = tile / tiles_n, tn = tile - tm * tiles_n;
     const int m0 = tm * BM, n0 = tn * BN;
@@ -232,73 +233,73 @@ __global__ __launch_bounds__(256, 1) void gemm_h16_dma_kernel(const HT *__restri
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // This wave loads, per k-tile, the 16-row blocks 4 wave + i (i = 0..3) of A and of B.
-    const int lr = lane >> 2, lc = (lane & 3) ^ ((lr >> 1) & 3);   // row within the block, chunk fetched
-    uint32_t a_eoff[4];
+    // This wave loads, per k-tile, the 8-row blocks 8 wave + i (i = 0..7) of A and of B.
+    const int lr = lane >> 3, lc = (lane & 7) ^ lr;        // row within the block, chunk fetched
+    uint32_t a_eoff[8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        int row = m0 + (wave * 4 + i) * 16 + lr;
+    for (int i = 0; i < 8; ++i) {
+        int row = m0 + (wave * 8 + i) * 8 + lr;
         row = row < M ? row : M - 1;                       // rows past the end: re-read the last row, never stored
         a_eoff[i] = (uint32_t)row * (uint32_t)K + (uint32_t)(lc * 8);
     }
     const uint32_t b_eoff = (uint32_t)(n0 + wave * 64 + lr) * (uint32_t)K + (uint32_t)(lc * 8);
-    const size_t b_istep = (size_t)16 * K;                  // Bt rows are padded to the tile: no clamp
+    const size_t b_istep = (size_t)8 * K;                   // Bt rows are padded to the tile: no clamp
     const int KT = K / BK;
-    auto issue_loads = [&](int kt_, int first, int count) {  // blocks first .. first+count-1 of the wave's eight
-        const int ktc = kt_ < KT ? kt_ : KT - 1;             // past the end: reload the last tile into a dead stage
-        const HT *Ak = A + (size_t)ktc * BK;
-        const HT *Bk = Bt + (size_t)ktc * BK;
-        unsigned char *st = smem_raw + (kt_ % NST) * STB;
-#pragma unroll
-        for (int q = first; q < first + count; ++q) {
-            if (q < 4) {
-                __builtin_amdgcn_global_load_lds(SJD_GPTR(Ak + a_eoff[q]), SJD_LPTR(st + (wave * 4 + q) * 1024), 16, 0, 0);
-            } else {
-                const int i = q - 4;
-                __builtin_amdgcn_global_load_lds(SJD_GPTR(Bk + i * b_istep + b_eoff),
-                                                 SJD_LPTR(st + OPB + (wave * 4 + i) * 1024), 16, 0, 0);
-            }
+    auto issue_load = [&](int kt_, int q) {                 // block q (0..15) of this wave's sixteen
+        const int ktc = kt_ < KT ? kt_ : KT - 1;            // past the end: reload the last tile into the dead stage
+        unsigned char *st = smem_raw + (kt_ & 1) * STB;
+        if (q < 8) {
+            __builtin_amdgcn_global_load_lds(SJD_GPTR(A + (size_t)ktc * BK + a_eoff[q]), SJD_LPTR(st + (wave * 8 + q) * 1024),
+                                             16, 0, 0);
+        } else {
+            const int i = q - 8;
+            __builtin_amdgcn_global_load_lds(SJD_GPTR(Bt + (size_t)ktc * BK + i * b_istep + b_eoff),
+                                             SJD_LPTR(st + OPB + (wave * 8 + i) * 1024), 16, 0, 0);
         }
     };
     v8 fa[2][MI], fb[2][NI];
-    // fragment (32 rows from row block r of the wave's sub-tile, k-step ks): row l32 is row l32 & 15 of
-    // 16-row block 2 r + (l32 >> 4); its chunk 2 ks + g sits in slot (2 ks + g) ^ swizzle(row)
-    const int rr = l32 & 15, swz = (rr >> 1) & 3;
-    const int frag_base = (l32 >> 4) * 1024 + rr * 64;
-    const int frag_k[2] = {frag_base + ((g ^ swz) << 4), frag_base + (((2 + g) ^ swz) << 4)};
+    // fragment (32 rows of row block r of the wave's sub-tile, k-step ks): row l32 is row l32 & 7 of
+    // 8-row block 4 r + (l32 >> 3); its chunk 2 ks + g sits in slot (2 ks + g) ^ (l32 & 7)
+    const int rr = l32 & 7;
+    const int frag_base = (l32 >> 3) * 1024 + rr * 128;
+    int frag_k[KSUB];
+#pragma unroll
+    for (int ks = 0; ks < KSUB; ++ks) frag_k[ks] = frag_base + (((2 * ks + g) ^ rr) << 4);
     auto read_one = [&](int stage, int ks, int buf, int r) {
         const unsigned char *st = smem_raw + stage * STB + frag_k[ks];
-        if (r < MI) fa[buf][r] = *reinterpret_cast<const v8 *>(st + (wm * 8 + 2 * r) * 1024);
-        else fb[buf][r - MI] = *reinterpret_cast<const v8 *>(st + OPB + (wn * 8 + 2 * (r - MI)) * 1024);
+        if (r < MI) fa[buf][r] = *reinterpret_cast<const v8 *>(st + (wm * 16 + 4 * r) * 1024);
+        else fb[buf][r - MI] = *reinterpret_cast<const v8 *>(st + OPB + (wn * 16 + 4 * (r - MI)) * 1024);
     };
 
-    issue_loads(0, 0, 8);
-    issue_loads(1, 0, 8);
-    issue_loads(2, 0, 8);
-    __builtin_amdgcn_s_waitcnt(0x0F70 | (16 & 15) | ((16 >> 4) << 14));  // vmcnt(16): tile 0 has landed
+#pragma unroll
+    for (int q = 0; q < 16; ++q) issue_load(0, q);
+    __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0): tile 0 has landed
     __builtin_amdgcn_s_barrier();
 #pragma unroll
     for (int r = 0; r < 8; ++r) read_one(0, 0, 0, r);
 
     for (int kt = 0; kt < KT; ++kt) {
-        const int cur = kt % NST, nxt = (kt + 1) % NST;
+        const int cur = kt & 1;
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
+        for (int ks = 0; ks < KSUB; ++ks) {
+            const int b = ks & 1;
 #pragma unroll
             for (int m = 0; m < 16; ++m) {
-                if (ks == 0) {
-                    if ((m & 1) == 0) read_one(cur, 1, 1, m >> 1);            // fragments of the second k-step
-                    if ((m & 3) == 1) issue_loads(kt + 3, m >> 2, 1);          // A blocks of tile kt+3
+                if (ks + 1 < KSUB) {
+                    // fragments of the next k-step, issued in the first half of this one
+                    if (m < 8) read_one(cur, ks + 1, b ^ 1, m);
                 } else {
-                    if (m < 8 && (m & 1) == 1) issue_loads(kt + 3, 4 + (m >> 1), 1);  // B blocks of tile kt+3
                     if (m == 8) {
-                        // tile kt+1 complete (only tiles kt+2, kt+3 may be in flight), own LDS reads done
-                        __builtin_amdgcn_s_waitcnt((16 & 15) | ((16 >> 4) << 14) | (7 << 4) | (0 << 8));
+                        // own loads of tile kt+1 complete, own LDS reads done; then everyone's
+                        __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
                         __builtin_amdgcn_s_barrier();
                     }
-                    if (m >= 8) read_one(nxt, 0, 0, m - 8);                    // first k-step of the next tile
+                    if (m >= 8) read_one(cur ^ 1, 0, b ^ 1, m - 8);   // first k-step of the next tile
                 }
-                acc[m / NI][m % NI] = Half16<HT>::mfma(fa[ks][m / NI], fb[ks][m % NI], acc[m / NI][m % NI]);
+                // the sixteen loads of tile kt+1 go out in the first two k-steps, one per two slots:
+                // the stage they fill was released by the barrier of the previous k-tile
+                if (ks < 2 && (m & 1) == 1) issue_load(kt + 1, ks * 8 + (m >> 1));
+                acc[m / NI][m % NI] = Half16<HT>::mfma(fa[b][m / NI], fb[b][m % NI], acc[m / NI][m % NI]);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -352,10 +353,13 @@ static void launch_tile(const HT *A, const HT *Bt, const float *bias, const floa
 //   past a matrix.
 template <typename HT, typename OutT, int EPI>
 static void pick_tile(const HT *A, const HT *Bt, const float *bias, const float *resid, OutT *C, int M, int N, int K,
-                      hipStream_t s) {
+                      int kernel, hipStream_t s) {
+    if (kernel == 1) return launch_tile<HT, 256, 128, 32, 2, OutT, EPI>(A, Bt, bias, resid, C, M, N, K, s);
+    if (kernel == 2) return launch_dma<HT, OutT, EPI>(A, Bt, bias, resid, C, M, N, K, s);
+    if (kernel == 3) return launch_tile<HT, 128, 128, 64, 1, OutT, EPI>(A, Bt, bias, resid, C, M, N, K, s);
     const long t128 = (long)((M + 127) / 128) * ((N + 127) / 128);
     const long t256 = (long)((M + 255) / 256) * ((N + 255) / 256);
-    const bool deep = K >= 3072 || (EPI == EPI_BIAS && K >= 1024 && N >= 1024);
+    const bool deep = K >= 3072 || (EPI == EPI_BIAS && K >= 768 && N >= 768);
     if (deep && M >= 256 && N >= 256 && t256 >= 256) launch_dma<HT, OutT, EPI>(A, Bt, bias, resid, C, M, N, K, s);
     else if (N >= 128 && M >= 256 && t128 >= 512) launch_tile<HT, 256, 128, 32, 2, OutT, EPI>(A, Bt, bias, resid, C, M, N, K, s);
     else launch_tile<HT, 128, 128, 64, 1, OutT, EPI>(A, Bt, bias, resid, C, M, N, K, s);
@@ -363,23 +367,23 @@ static void pick_tile(const HT *A, const HT *Bt, const float *bias, const float 
 
 template <typename HT, typename OutT>
 void launch_gemm_h16(const HT *A, const HT *Bt, const float *bias, const float *resid, OutT *C, int M, int N, int K,
-                     Epi epi, hipStream_t s) {
+                     Epi epi, hipStream_t s, int kernel) {
     if (M <= 0 || N <= 0) return;
     if constexpr (sizeof(OutT) == 4) {
-        if (epi == EPI_BIAS_RESIDUAL) pick_tile<HT, float, EPI_BIAS_RESIDUAL>(A, Bt, bias, resid, C, M, N, K, s);
-        else pick_tile<HT, float, EPI_BIAS>(A, Bt, bias, resid, C, M, N, K, s);
+        if (epi == EPI_BIAS_RESIDUAL) pick_tile<HT, float, EPI_BIAS_RESIDUAL>(A, Bt, bias, resid, C, M, N, K, kernel, s);
+        else pick_tile<HT, float, EPI_BIAS>(A, Bt, bias, resid, C, M, N, K, kernel, s);
     } else {
-        if (epi == EPI_BIAS_GELU) pick_tile<HT, HT, EPI_BIAS_GELU>(A, Bt, bias, resid, C, M, N, K, s);
-        else pick_tile<HT, HT, EPI_BIAS>(A, Bt, bias, resid, C, M, N, K, s);
+        if (epi == EPI_BIAS_GELU) pick_tile<HT, HT, EPI_BIAS_GELU>(A, Bt, bias, resid, C, M, N, K, kernel, s);
+        else pick_tile<HT, HT, EPI_BIAS>(A, Bt, bias, resid, C, M, N, K, kernel, s);
     }
 }
 template void launch_gemm_h16<bf16, bf16>(const bf16 *, const bf16 *, const float *, const float *, bf16 *, int, int,
-                                          int, Epi, hipStream_t);
+                                          int, Epi, hipStream_t, int);
 template void launch_gemm_h16<bf16, float>(const bf16 *, const bf16 *, const float *, const float *, float *, int, int,
-                                           int, Epi, hipStream_t);
+                                           int, Epi, hipStream_t, int);
 template void launch_gemm_h16<f16, f16>(const f16 *, const f16 *, const float *, const float *, f16 *, int, int, int,
-                                        Epi, hipStream_t);
+                                        Epi, hipStream_t, int);
 template void launch_gemm_h16<f16, float>(const f16 *, const f16 *, const float *, const float *, float *, int, int,
-                                          int, Epi, hipStream_t);
+                                          int, Epi, hipStream_t, int);
 
 }  // namespace sjd

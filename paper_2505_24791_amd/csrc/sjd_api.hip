@@ -338,10 +338,11 @@ int run_jacobi(sjd_flow *f, int j, const float *z, float *x, int batch, const sj
 bool fast_decode_ok(const sjd_flow *f) {
     return f->cfg.dtype != SJD_DTYPE_F32 && f->cfg.width / f->cfg.n_heads == 64 && f->cfg.max_batch <= 256;
 }
-// Fragment-major operands: up to 64 rows and a width the fused LayerNorm projection covers.
+// Fragment-major operands: a width the fused LayerNorm projection covers.
 bool frag_ok(const sjd_flow *f, int batch) {
     const int W = f->cfg.width;
-    return fast_decode_ok(f) && batch <= 64 && (W == 256 || W == 512 || W == 768 || W == 1024);
+    (void)batch;
+    return fast_decode_ok(f) && (W == 256 || W == 512 || W == 768 || W == 1024);
 }
 
 // Launches of one step (all layers, head, advance) for position *t_dev, on stream s.
@@ -701,6 +702,28 @@ int sjd_sample(sjd_flow *f, const float *z_dev, float *x_dev, int batch, uint32_
     if (stats_host)
         for (int j = 0; j < c.n_blocks; ++j) HIP_TRY(hipEventElapsedTime(&stats_host->block_ms[j], f->ev[j], f->ev[j + 1]));
     if (any_nonfinite) return fail(SJD_ENONFINITE, "a sample ended a Jacobi block with a non-finite difference norm");
+    return SJD_OK;
+}
+
+int sjd_op_linear_h16(int dtype, int kernel, const void *a_dev, const void *wt_dev, const float *bias_dev,
+                      float *resid_out_dev, void *c_dev, int M, int N, int K, int epilogue, void *hip_stream) {
+    if (!a_dev || !wt_dev || !bias_dev) return fail(SJD_EINVAL, "null device pointer");
+    if (dtype != SJD_DTYPE_BF16 && dtype != SJD_DTYPE_F16) return fail(SJD_EINVAL, "dtype must be a 16-bit mode");
+    if (M < 1 || N < 1 || K < 64 || K % 64) return fail(SJD_EINVAL, "need M, N >= 1 and K a positive multiple of 64");
+    if (kernel < 0 || kernel > 3) return fail(SJD_EINVAL, "kernel must be 0..3");
+    if (epilogue < 0 || epilogue > 2) return fail(SJD_EINVAL, "epilogue must be 0..2");
+    if (epilogue == 2 ? !resid_out_dev : !c_dev) return fail(SJD_EINVAL, "null output pointer");
+    hipStream_t s = (hipStream_t)hip_stream;
+    const Epi epi = (Epi)epilogue;
+    if (dtype == SJD_DTYPE_BF16) {
+        if (epilogue == 2) launch_gemm_h16<bf16, float>((const bf16 *)a_dev, (const bf16 *)wt_dev, bias_dev, resid_out_dev, resid_out_dev, M, N, K, epi, s, kernel);
+        else launch_gemm_h16<bf16, bf16>((const bf16 *)a_dev, (const bf16 *)wt_dev, bias_dev, nullptr, (bf16 *)c_dev, M, N, K, epi, s, kernel);
+    } else {
+        if (epilogue == 2) launch_gemm_h16<f16, float>((const f16 *)a_dev, (const f16 *)wt_dev, bias_dev, resid_out_dev, resid_out_dev, M, N, K, epi, s, kernel);
+        else launch_gemm_h16<f16, f16>((const f16 *)a_dev, (const f16 *)wt_dev, bias_dev, nullptr, (f16 *)c_dev, M, N, K, epi, s, kernel);
+    }
+    HIP_TRY(hipStreamSynchronize(s));
+    HIP_TRY(hipGetLastError());
     return SJD_OK;
 }
 

@@ -144,6 +144,9 @@ BF16_CASES = [
     # the same with at most 32 rows (two row blocks, 16 waves splitting K)
     ("bf16_frag32", wl.FlowConfig("bf16_frag32", n_blocks=2, n_layers=1, width=256, n_heads=4, seq_len=24,
                                   token_dim=8, batch=19, bf16=True), True),
+    # 70 samples: two row groups of the single-token kernels, the second with 6 live rows
+    ("bf16_frag_groups", wl.FlowConfig("bf16_frag_groups", n_blocks=2, n_layers=1, width=256, n_heads=4, seq_len=20,
+                                       token_dim=8, batch=70, bf16=True), True),
     # head size 32: the generic attention path
     ("bf16_dh32", wl.FlowConfig("bf16_dh32", n_blocks=2, n_layers=1, width=64, n_heads=2, seq_len=50, token_dim=6,
                                 batch=3, bf16=True), True),
