@@ -22,6 +22,11 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_F32_TFLOPS = 157.3     # MI355X fp32 vector
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
+# Bytes per launch that the L2s requested from / wrote to the memory side, from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs of `bench.py --counters`, scaled by what the same counters read for a 256 MiB copy
+# (profiles/bench_c2_hbm_counters.md).  Keyed by (workload, kernel family); anything else reports null.
+MEASURED_TRAFFIC_BYTES = {("C2", "decode_gemm"): 2.97e6}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -30,10 +35,15 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C2", help="C1..C5 (C2 is the configuration the metric is quoted on)")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch (0 = as configured)")
+    ap.add_argument("--seq-len", type=int, default=0, help="override the workload's token count T (0 = as configured)")
     ap.add_argument("--tau", type=float, default=0.0, help="override tau (0 = as configured)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-seq", action="store_true", help="skip the GPU all-sequential baseline")
     ap.add_argument("--cpu-samples", type=int, default=0, help="samples for the CPU baseline (0 = one per thread)")
+    ap.add_argument("--counters", action="store_true",
+                    help="for runs under rocprofv3 --pmc: a plain 256 MiB device copy five times (the known-size "
+                         "kernel that hardware traffic counters are scaled by), then ONE pass of the hot path "
+                         "block by block with plain launches (no graph replay), progress on stderr, no timing")
     return ap.parse_args()
 
 
@@ -55,6 +65,8 @@ def main() -> int:
     cfg = wl.CONFIGS[args.workload]
     if args.batch:
         cfg = cfg.with_(batch=args.batch)
+    if args.seq_len:
+        cfg = cfg.with_(seq_len=args.seq_len)
     tau = args.tau if args.tau > 0 else cfg.tau
     K = cfg.n_blocks
     mask_sel = ~1 & ((1 << K) - 1)
@@ -68,8 +80,27 @@ def main() -> int:
     opts = sjd.JacobiOpts(tau=tau)
     torch.cuda.synchronize()
 
+    if args.counters:
+        def say(msg):
+            print(f"[counters] {msg}", file=sys.stderr, flush=True)
+        src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        say("copy kernel done: 5 x 256 MiB read + 256 MiB written")
+        flow.profile_enable(range(sjd.PROF_FAMILIES))      # plain launches instead of graph replay
+        cur = flow.sequential_inverse_block(0, z)
+        say("block 0 (sequential) done")
+        for j in range(1, K):
+            cur, _, passes, _ = flow.jacobi_inverse_block(j, cur, opts)
+            say(f"block {j} (Jacobi) done: {passes} passes")
+        flow.close()
+        return 0
+
     def run(mask, n):
-        stats = None
+        stats = iters = None
         for _ in range(n):
             _, stats, iters = flow.sample(z, mask, opts, out=x, want_iters=True)
         return stats, iters
@@ -108,7 +139,9 @@ def main() -> int:
         achieved = d["bytes"] / launches / avg_s / 1e9
         roof = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": achieved / PEAK_HBM_GBS, "traffic": None}
-    roof.update({"kernel_family": dominant, "launches_per_step": launches / args.steps,
+    if not (args.batch or args.seq_len):
+        roof["traffic"] = MEASURED_TRAFFIC_BYTES.get((cfg.name, dominant))
+    roof.update({"kernel_family": dominant, "algorithmic_bytes_per_launch": d["bytes"] / launches, "launches_per_step": launches / args.steps,
                  "avg_launch_us": avg_s * 1e6, "family_ms_per_step": fam_ms})
     families = {}
     for k, v in prof.items():
