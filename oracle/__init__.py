@@ -69,6 +69,13 @@ class Oracle:
         assert self.lib.orc_forward_block(C.byref(_as_cfg(cfg)), self._w(blob), j, self._p(x), self._p(y)) == 0
         return y
 
+    def forward_block_logdet(self, cfg, blob, j, x) -> Tuple[np.ndarray, float]:
+        """eq. 4 for one sample and log |det dy/dx| of the block (= -sum alpha)."""
+        x = self._r(x); y = np.empty_like(x); ld = np.zeros(1, self.dtype)
+        assert self.lib.orc_forward_block_logdet(C.byref(_as_cfg(cfg)), self._w(blob), j, self._p(x), self._p(y),
+                                                 self._p(ld)) == 0
+        return y, float(ld[0])
+
     def sequential_inverse_block_naive(self, cfg, blob, j, z, fill: float = 0.0) -> np.ndarray:
         z = self._r(z); x = np.empty_like(z)
         assert self.lib.orc_sequential_inverse_block_naive(C.byref(_as_cfg(cfg)), self._w(blob), j, self._p(z),
@@ -124,6 +131,13 @@ class Oracle:
         x = self._r(x); z = np.empty_like(x)
         assert self.lib.orc_forward(C.byref(_as_cfg(cfg)), self._w(blob), self._p(x), self._p(z), x.shape[0]) == 0
         return z
+
+    def forward_logdet(self, cfg, blob, x) -> Tuple[np.ndarray, np.ndarray]:
+        """Whole forward map (blocks K-1 .. 0) and its log-determinant per sample."""
+        x = self._r(x); z = np.empty_like(x); ld = np.zeros(x.shape[0], self.dtype)
+        assert self.lib.orc_forward_logdet(C.byref(_as_cfg(cfg)), self._w(blob), self._p(x), self._p(z), self._p(ld),
+                                           x.shape[0]) == 0
+        return z, ld
 
     # -- primitives
     def layernorm(self, x, g, b) -> np.ndarray:

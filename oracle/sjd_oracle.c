@@ -341,8 +341,11 @@ EXPORT int orc_cond(const orc_config *c, const float *blob, int j, const real *x
     return 0;
 }
 
-/* eq. 4 for block j: canonical order in (x), canonical order out (y). */
-EXPORT int orc_forward_block(const orc_config *c, const float *blob, int j, const real *x, real *y) {
+/* eq. 4 for block j: canonical order in (x), canonical order out (y).  If logdet is not NULL it
+ * receives log |det dy/dx| of this block: the map is triangular in the processing order with
+ * diagonal exp(-alpha), so the log-determinant is minus the sum of all alpha (the term that the
+ * change-of-variables formula, eq. 1, adds per block; token 1 has alpha = 0). */
+static int forward_block_impl(const orc_config *c, const float *blob, int j, const real *x, real *y, real *logdet) {
     int T = c->seq_len, D = c->token_dim, rev = (c->reverse_mask >> j) & 1;
     block_w bw; cond_ws w;
     if (c->n_layers > ORC_MAX_LAYERS || ws_alloc(c, &w)) return -1;
@@ -350,15 +353,26 @@ EXPORT int orc_forward_block(const orc_config *c, const float *blob, int j, cons
     real *u = (real *)malloc(sizeof(real) * T * D), *v = (real *)malloc(sizeof(real) * T * D);
     flip_tokens(c, rev, x, u);
     cond_full(c, &bw, u, &w);
+    double sum_alpha = 0.0;
     for (int l = 0; l < T; ++l)
         for (int d = 0; d < D; ++d) {
             real mu, al;
             params_of(c, &w, l, d, &mu, &al);
             v[(size_t)l * D + d] = (u[(size_t)l * D + d] - mu) * (real)exp((double)(-al));
+            sum_alpha += (double)al;
         }
+    if (logdet) *logdet = (real)(-sum_alpha);
     flip_tokens(c, rev, v, y);
     free(u); free(v); ws_free(&w);
     return 0;
+}
+
+EXPORT int orc_forward_block(const orc_config *c, const float *blob, int j, const real *x, real *y) {
+    return forward_block_impl(c, blob, j, x, y, NULL);
+}
+
+EXPORT int orc_forward_block_logdet(const orc_config *c, const float *blob, int j, const real *x, real *y, real *logdet) {
+    return forward_block_impl(c, blob, j, x, y, logdet);
 }
 
 /* eq. 5 by the definition: for every token a full conditioner pass over the sequence built so
@@ -529,6 +543,29 @@ EXPORT int orc_forward(const orc_config *c, const float *blob, const real *x, re
             real *t = cur; cur = nxt; nxt = t;
         }
         memcpy(z + (size_t)b * n, cur, sizeof(real) * n);
+        free(cur); free(nxt);
+    }
+    return fail ? -1 : 0;
+}
+
+/* The same with the log-determinant of the whole forward map per sample: the sum over blocks (eq. 2's
+ * composition, so the Jacobians multiply). */
+EXPORT int orc_forward_logdet(const orc_config *c, const float *blob, const real *x, real *z, real *logdet, int batch) {
+    size_t n = (size_t)c->seq_len * c->token_dim;
+    int fail = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < batch; ++b) {
+        real *cur = (real *)malloc(sizeof(real) * n), *nxt = (real *)malloc(sizeof(real) * n);
+        memcpy(cur, x + (size_t)b * n, sizeof(real) * n);
+        double total = 0.0;
+        for (int j = c->n_blocks - 1; j >= 0; --j) {
+            real ld = 0;
+            if (forward_block_impl(c, blob, j, cur, nxt, &ld)) fail = 1;
+            total += (double)ld;
+            real *t = cur; cur = nxt; nxt = t;
+        }
+        memcpy(z + (size_t)b * n, cur, sizeof(real) * n);
+        logdet[b] = (real)total;
         free(cur); free(nxt);
     }
     return fail ? -1 : 0;

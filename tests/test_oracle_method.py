@@ -308,3 +308,61 @@ def test_selective_result_close_to_sequential_within_tau_scale(orc64):
     assert np.all(iters[1:] < 10) and np.all(iters[0] == cfg.seq_len - 1)
     xr0, _, _ = orc64.sample(cfg, blob, z, ~1, 0.0)
     assert np.abs(xr0 - x).max() < 1e-11
+
+
+# ---- log-determinant of the forward map (eq. 1's change-of-variables term for eq. 4) -----------
+
+def _numerical_jacobian(fn, x, h=1e-6):
+    n = x.size
+    J = np.empty((n, n))
+    for i in range(n):
+        e = np.zeros(n); e[i] = h
+        J[:, i] = (fn((x.reshape(-1) + e).reshape(x.shape)).reshape(-1)
+                   - fn((x.reshape(-1) - e).reshape(x.shape)).reshape(-1)) / (2 * h)
+    return J
+
+
+@pytest.mark.parametrize("T,D", [(3, 2), (5, 1), (4, 3)])
+def test_logdet_equals_log_determinant_of_the_numerical_jacobian(orc64, T, D):
+    cfg, blob, z = _flow(T, seed=3, D=D)
+    x = z[0].astype(np.float64)
+    total = 0.0
+    cur = x
+    for j in range(cfg.n_blocks - 1, -1, -1):
+        y, ld = orc64.forward_block_logdet(cfg, blob, j, cur)
+        J = _numerical_jacobian(lambda v: orc64.forward_block(cfg, blob, j, v), cur)
+        sign, logabs = np.linalg.slogdet(J)
+        assert sign > 0                                   # diagonal exp(-alpha) > 0
+        assert abs(logabs - ld) <= 1e-6
+        np.testing.assert_array_equal(y, orc64.forward_block(cfg, blob, j, cur))
+        total += ld
+        cur = y
+    # the whole flow: Jacobians multiply, log-determinants add
+    zf, ld_all = orc64.forward_logdet(cfg, blob, x[None])
+    np.testing.assert_array_equal(zf[0], cur)
+    assert abs(ld_all[0] - total) <= 1e-12
+    Jf = _numerical_jacobian(lambda v: orc64.forward(cfg, blob, v[None])[0], x)
+    assert abs(np.linalg.slogdet(Jf)[1] - total) <= 1e-5
+
+
+def test_logdet_closed_forms(orc64, orc32):
+    """Head weights zero: alpha is the head's bias for every token but the first, whatever the
+    input, so logdet = -(T-1) * sum_d b_alpha[d] per block; zero bias too: volume preserving."""
+    cfg = wl.tiny_config(T=6, D=3, K=3)
+    blob = wl.make_weights(cfg, seed_base=77, perturb_affine=True, std=0.1)
+    views = wl.blob_views(cfg, blob)
+    expect = 0.0
+    for j, v in enumerate(views):
+        v["w_head"][...] = 0.0
+        v["b_head"][...] = 0.0
+        v["b_head"][cfg.token_dim:] = np.float32(0.1 * (j + 1)) * np.arange(1, cfg.token_dim + 1, dtype=np.float32)
+        expect += -(cfg.seq_len - 1) * float(v["b_head"][cfg.token_dim:].astype(np.float64).sum())
+    x = wl.make_latent(cfg, batch=2, seed=1)
+    for orc, tol in ((orc64, 1e-12), (orc32, 1e-5)):
+        _, ld = orc.forward_logdet(cfg, blob, x)
+        np.testing.assert_allclose(ld, [expect, expect], atol=tol * 10)
+    for v in views:
+        v["b_head"][...] = 0.0
+    z, ld = orc64.forward_logdet(cfg, blob, x)
+    np.testing.assert_array_equal(ld, [0.0, 0.0])
+    np.testing.assert_array_equal(z, x.astype(np.float64))
