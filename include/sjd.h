@@ -79,7 +79,8 @@ typedef struct {
 typedef struct {
     float tau;              /* stop a sample when its delta < tau (strict).  tau = 0 runs to the cap. */
     int32_t criterion;      /* 0: delta = mean over (l, d) of |x^t - x^(t-1)|;  1: the maximum (Alg. 1 as printed) */
-    int32_t init;           /* 0: x^0 = 0 (Alg. 1);  1: x^0 = the block's input (Sec. 4.3, initialisation study) */
+    int32_t init;           /* 0: x^0 = 0 (Alg. 1);  1: x^0 = the block's input;  2: x^0 = what x_dev holds on entry,
+                               e.g. the caller's own N(0, I) draw (the initialisation study of Sec. 4.3) */
     int32_t max_iters;      /* 0 or >= T: the cap is T (Prop. 3.2: the T-th iterate is exact); else a lower cap */
     int32_t drop_converged; /* 1: converged samples leave the batch the conditioner runs on;  0: they stay
                                (and are ignored).  Results and counts are the same either way. */
@@ -132,6 +133,34 @@ SJD_API int sjd_jacobi_inverse_block(sjd_flow *flow, int block, const float *z_d
                              const sjd_jacobi_opts *opts, int32_t *iters_per_sample_host,
                              int32_t *block_iters_host, void *hip_stream);
 
+/* Jacobi decoding of one block with a per-pass record (the convergence curves of Sec. 4.3 and
+ * App. B: how fast the iterates approach the sequential solution).  Works like
+ * sjd_jacobi_inverse_block and additionally fills, for pass p = 0 .. passes-1 and sample b,
+ *   delta_trace_host[p * batch + b] = that sample's delta after pass p+1 (criterion of opts),
+ *   err_trace_host  [p * batch + b] = || x^(p+1) - x_ref ||_2 over the sample's T*D values
+ * (HOST arrays of at least cap * batch floats, cap = the pass cap of opts; err_trace_host may be
+ * NULL; x_ref_dev is DEVICE memory [batch, T, D], typically the sequential inverse, and may be NULL
+ * when no error trace is wanted).  A sample that has stopped keeps its last iterate, so its
+ * entries repeat from then on. */
+SJD_API int sjd_jacobi_trace_block(sjd_flow *flow, int block, const float *z_dev, float *x_dev, const float *x_ref_dev,
+                                   int batch, const sjd_jacobi_opts *opts, float *delta_trace_host,
+                                   float *err_trace_host, int32_t *iters_per_sample_host, int32_t *block_iters_host,
+                                   void *hip_stream);
+
+/* Forward (data -> latent) map of block `block`, eq. 4: one whole-sequence conditioner pass on
+ * x_dev, then y = (x - mu) * exp(-alpha) for every token (the first processed token is copied).
+ * logdet_dev (nullable, DEVICE, [batch] float32) receives log |det dy/dx| = -sum alpha of each
+ * sample, the block's term in the change-of-variables formula (eq. 1); with accumulate != 0 it is
+ * added to what logdet_dev holds.  x_dev and y_dev may not overlap. */
+SJD_API int sjd_forward_block(sjd_flow *flow, int block, const float *x_dev, float *y_dev, float *logdet_dev,
+                              int accumulate, int batch, void *hip_stream);
+
+/* The whole forward map z_K = f^-1(x): blocks K-1 .. 0 of eq. 4 (the inverse of sjd_sample's cascade,
+ * eq. 2), K conditioner passes in all.  logdet_dev (nullable, DEVICE, [batch]) receives the sum of
+ * the blocks' log-determinants. */
+SJD_API int sjd_forward(sjd_flow *flow, const float *x_dev, float *z_dev, float *logdet_dev, int batch,
+                        void *hip_stream);
+
 /* Sequential inverse of block `block` (Sec. 3.1, eq. 5) with a key/value cache (Sec. 3.5):
  * T-1 single-token conditioner steps. */
 SJD_API int sjd_sequential_inverse_block(sjd_flow *flow, int block, const float *z_dev, float *x_dev, int batch,
@@ -140,7 +169,8 @@ SJD_API int sjd_sequential_inverse_block(sjd_flow *flow, int block, const float 
 /* The whole cascade x = f_0(...f_{K-1}(z_K)) (Sec. 3.1, eq. 2) with a per-block mode (Sec. 3.5):
  * bit j of jacobi_mask set => block j by Jacobi decoding, clear => sequentially.  ~1u is the
  * selective strategy, 0 the sequential baseline, ~0u Jacobi everywhere.  stats_host (nullable) and
- * iters_host (nullable, [K][batch] passes per block and sample) are filled on return. */
+ * iters_host (nullable, [K][batch] passes per block and sample) are filled on return.
+ * opts->init = 2 is refused here (there is no caller-held first iterate inside the cascade). */
 SJD_API int sjd_sample(sjd_flow *flow, const float *z_dev, float *x_dev, int batch, uint32_t jacobi_mask,
                const sjd_jacobi_opts *opts, sjd_stats *stats_host, int32_t *iters_host, void *hip_stream);
 

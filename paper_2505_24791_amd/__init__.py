@@ -24,7 +24,8 @@ PROF_FAMILIES = 6
 PROF_NAMES = ("gemm", "attention", "epilogue", "decode_gemm", "decode_attn", "other")
 
 EXPORTS = ("sjd_flow_create", "sjd_flow_load_weights", "sjd_jacobi_inverse_block", "sjd_sequential_inverse_block",
-           "sjd_sample", "sjd_conditioner", "sjd_op_linear_h16", "sjd_profile_enable", "sjd_profile_read", "sjd_flow_device_bytes",
+           "sjd_sample", "sjd_conditioner", "sjd_op_linear_h16", "sjd_jacobi_trace_block", "sjd_forward_block",
+           "sjd_forward", "sjd_profile_enable", "sjd_profile_read", "sjd_flow_device_bytes",
            "sjd_last_error", "sjd_flow_destroy")
 
 
@@ -73,6 +74,11 @@ def load_library() -> C.CDLL:
     lib.sjd_sequential_inverse_block.argtypes = [vp, C.c_int, fp, fp, C.c_int, vp]
     lib.sjd_sample.argtypes = [vp, fp, fp, C.c_int, C.c_uint32, C.POINTER(SjdJacobiOpts), C.POINTER(SjdStats), i32p, vp]
     lib.sjd_conditioner.argtypes = [vp, C.c_int, fp, fp, fp, C.c_int, vp]
+    lib.sjd_jacobi_trace_block.argtypes = [vp, C.c_int, vp, vp, vp, C.c_int, C.POINTER(SjdJacobiOpts),
+                                           C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_int32),
+                                           C.POINTER(C.c_int32), vp]
+    lib.sjd_forward_block.argtypes = [vp, C.c_int, vp, vp, vp, C.c_int, C.c_int, vp]
+    lib.sjd_forward.argtypes = [vp, vp, vp, vp, C.c_int, vp]
     lib.sjd_op_linear_h16.argtypes = [C.c_int, C.c_int, vp, vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, vp]
     lib.sjd_profile_enable.argtypes = [vp, C.c_uint32]
     lib.sjd_profile_read.argtypes = [vp, C.POINTER(SjdProfile), C.c_int]
@@ -183,11 +189,12 @@ class Flow:
         _check(self.lib.sjd_conditioner(self._h, block, _dev(x, self._shape(B)), _dev(mu), _dev(al), B, _stream_ptr()))
         return mu, al
 
-    def jacobi_inverse_block(self, block: int, z, opts: JacobiOpts, allow_nonfinite: bool = False):
-        """Returns (x, iters_per_sample int32 [B], passes_launched, rc)."""
+    def jacobi_inverse_block(self, block: int, z, opts: JacobiOpts, allow_nonfinite: bool = False, x0=None):
+        """Returns (x, iters_per_sample int32 [B], passes_launched, rc).  With opts.init == 2 the first
+        iterate is ``x0`` (copied, not modified)."""
         import torch
         B = z.shape[0]
-        x = torch.empty_like(z)
+        x = torch.empty_like(z) if x0 is None else x0.detach().clone().contiguous()
         iters = np.zeros(B, np.int32)
         passes = C.c_int32(0)
         o = opts.c()
@@ -195,6 +202,48 @@ class Flow:
                                                       iters.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(passes),
                                                       _stream_ptr()), allow_nonfinite)
         return x, iters, int(passes.value), rc
+
+    def jacobi_trace_block(self, block: int, z, opts: JacobiOpts, x_ref=None, x0=None):
+        """Jacobi decoding with the per-pass record.  Returns (x, iters [B], passes, delta [passes, B],
+        err [passes, B] or None)."""
+        import torch
+        B = z.shape[0]
+        T = self.cfg.seq_len
+        cap = opts.max_iters if 0 < opts.max_iters < T else T
+        x = torch.empty_like(z) if x0 is None else x0.detach().clone().contiguous()
+        iters = np.zeros(B, np.int32)
+        passes = C.c_int32(0)
+        delta = np.zeros((cap, B), np.float32)
+        err = np.zeros((cap, B), np.float32) if x_ref is not None else None
+        o = opts.c()
+        fp = C.POINTER(C.c_float)
+        _check(self.lib.sjd_jacobi_trace_block(
+            self._h, block, _dev(z, self._shape(B)), _dev(x), _dev(x_ref, self._shape(B)) if x_ref is not None else None,
+            B, C.byref(o), delta.ctypes.data_as(fp), err.ctypes.data_as(fp) if err is not None else None,
+            iters.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(passes), _stream_ptr()))
+        n = int(passes.value)
+        return x, iters, n, delta[:n], (err[:n] if err is not None else None)
+
+    def forward_block(self, block: int, x, logdet=None, accumulate: bool = False):
+        """eq. 4 for one block.  Returns (y, logdet [B] float32 device tensor)."""
+        import torch
+        B = x.shape[0]
+        y = torch.empty_like(x)
+        if logdet is None:
+            logdet = torch.zeros(B, dtype=torch.float32, device=x.device)
+        _check(self.lib.sjd_forward_block(self._h, block, _dev(x, self._shape(B)), _dev(y), C.c_void_p(logdet.data_ptr()),
+                                          1 if accumulate else 0, B, _stream_ptr()))
+        return y, logdet
+
+    def forward(self, x):
+        """The whole forward map (blocks K-1 .. 0).  Returns (z, logdet [B])."""
+        import torch
+        B = x.shape[0]
+        z = torch.empty_like(x)
+        logdet = torch.zeros(B, dtype=torch.float32, device=x.device)
+        _check(self.lib.sjd_forward(self._h, _dev(x, self._shape(B)), _dev(z), C.c_void_p(logdet.data_ptr()), B,
+                                    _stream_ptr()))
+        return z, logdet
 
     def sequential_inverse_block(self, block: int, z):
         import torch

@@ -182,6 +182,10 @@ void launch_decode_epilogue(const float *p, const float *z, float *x, int B, int
                             hipStream_t s);
 
 // mu/alpha extraction for sjd_conditioner: shifted parameters in canonical order.
+void launch_jacobi_trace(const float *x, const float *x_ref, JacobiState st, float *delta_out, float *err_out, int B,
+                         int T, int D, hipStream_t s);
+void launch_forward_epilogue(const float *p, const float *x, float *y, float *logdet, int B, int T, int D, int reversed,
+                             int accumulate, hipStream_t s);
 void launch_split_params(const float *p, float *mu, float *alpha, int B, int T, int D, int reversed, hipStream_t s);
 
 // Weight preparation on the device: dst[n, k] (16-bit, row length ldb, zero padded) = src[k, n] (float [K, N]).

@@ -158,7 +158,7 @@ __global__ __launch_bounds__(256) void jacobi_init_kernel(const float *__restric
                                                           JacobiState st, int B, size_t n_per_sample, int init) {
     const size_t n = (size_t)B * n_per_sample;
     for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < n; e += (size_t)gridDim.x * 256)
-        x[e] = init == 1 ? z[e] : 0.f;
+        if (init != 2) x[e] = init == 1 ? z[e] : 0.f;   // init 2: the caller's x^0 is already in x
     if (blockIdx.x == 0) {
         for (int b = threadIdx.x; b < B; b += 256) {
             st.iters[b] = 0; st.done[b] = 0; st.delta[b] = 0.f; st.active_in[b] = b; st.active_out[b] = b;
@@ -173,6 +173,73 @@ void launch_jacobi_init(const float *z, float *x, JacobiState st, int B, int T, 
     if (grid > 2048) grid = 2048;
     if (grid < 1) grid = 1;
     hipLaunchKernelGGL(jacobi_init_kernel, dim3(grid), dim3(256), 0, s, z, x, st, B, (size_t)T * D, init);
+}
+
+// Per-pass convergence record: delta of the pass just made and the l2 distance of the newest
+// iterate to a reference solution, one workgroup per sample (fixed summation order).
+__global__ __launch_bounds__(256) void jacobi_trace_kernel(const float *__restrict__ x, const float *__restrict__ x_ref,
+                                                           JacobiState st, float *__restrict__ delta_out,
+                                                           float *__restrict__ err_out, int n) {
+    __shared__ float part[4];
+    const int b = blockIdx.x;
+    if (threadIdx.x == 0) delta_out[b] = st.delta[b];
+    if (!x_ref) return;
+    float acc = 0.f;
+    for (int e = threadIdx.x; e < n; e += 256) {
+        const float d = x[(size_t)b * n + e] - x_ref[(size_t)b * n + e];
+        acc = fmaf(d, d, acc);
+    }
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) err_out[b] = sqrtf(((part[0] + part[1]) + part[2]) + part[3]);
+}
+
+void launch_jacobi_trace(const float *x, const float *x_ref, JacobiState st, float *delta_out, float *err_out, int B,
+                         int T, int D, hipStream_t s) {
+    if (B <= 0) return;
+    hipLaunchKernelGGL(jacobi_trace_kernel, dim3(B), dim3(256), 0, s, x, x_ref, st, delta_out, err_out, T * D);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Forward map of one block (eq. 4) from the head output of one conditioner pass on the block's
+// input: y = (x - mu) * exp(-alpha) with the one-token shift, and log |det dy/dx| = -sum alpha
+// (eq. 1's change-of-variables term).  One workgroup per sample; fixed summation order.
+__global__ __launch_bounds__(256) void forward_epilogue_kernel(const float *__restrict__ p, const float *__restrict__ x,
+                                                               float *__restrict__ y, float *__restrict__ logdet,
+                                                               int T, int D, int reversed, int accumulate) {
+    __shared__ float part[4];
+    const int b = blockIdx.x;
+    const int n = T * D;
+    const float *pr = p + (size_t)b * T * 2 * D;
+    float acc = 0.f;
+    for (int e = threadIdx.x; e < n; e += 256) {
+        const int l = e / D, d = e - l * D;
+        const int tok = reversed ? T - 1 - l : l;
+        const size_t idx = ((size_t)b * T + tok) * D + d;
+        float v = x[idx];
+        if (l > 0) {
+            const float mu = pr[(size_t)(l - 1) * 2 * D + d];
+            const float al = pr[(size_t)(l - 1) * 2 * D + D + d];
+            v = (v - mu) * expf(-al);
+            acc += al;
+        }
+        y[idx] = v;
+    }
+    if (!logdet) return;
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const float ld = -(((part[0] + part[1]) + part[2]) + part[3]);
+        logdet[b] = accumulate ? logdet[b] + ld : ld;
+    }
+}
+
+void launch_forward_epilogue(const float *p, const float *x, float *y, float *logdet, int B, int T, int D, int reversed,
+                             int accumulate, hipStream_t s) {
+    if (B <= 0) return;
+    hipLaunchKernelGGL(forward_epilogue_kernel, dim3(B), dim3(256), 0, s, p, x, y, logdet, T, D, reversed, accumulate);
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -69,6 +69,7 @@ struct sjd_flow {
     float *pp[2] = {nullptr, nullptr};          // block outputs inside sjd_sample
     JacobiState st{};
     int32_t *active[2] = {nullptr, nullptr};
+    float *trace = nullptr;                     // per-pass record: delta [T][B], then l2 error [T][B]
     int32_t *host_pin = nullptr;                // pinned: [0] n_active, [1] nonfinite, [2..] iters[B]
     // sequential fast path: device step counter, ticket, capture stream, one graph per (block, batch)
     int32_t *t_dev = nullptr;
@@ -290,14 +291,16 @@ int check_opts(const sjd_jacobi_opts *o) {
     if (!o) return fail(SJD_EINVAL, "null options");
     if (o->tau != o->tau) return fail(SJD_EINVAL, "tau is NaN");
     if (o->criterion != 0 && o->criterion != 1) return fail(SJD_EINVAL, "criterion must be 0 or 1");
-    if (o->init != 0 && o->init != 1) return fail(SJD_EINVAL, "init must be 0 (zeros) or 1 (block input)");
+    if (o->init < 0 || o->init > 2) return fail(SJD_EINVAL, "init must be 0 (zeros), 1 (block input) or 2 (x_dev as passed)");
     if (o->max_iters < 0) return fail(SJD_EINVAL, "max_iters is negative");
     return SJD_OK;
 }
 
 // Alg. 1 for one block.  iters_pin (pinned host, [batch]) receives per-sample pass counts.
+// With `trace` every pass also records each sample's delta and (x_ref given) the l2 distance of its
+// newest iterate to x_ref into f->trace.
 int run_jacobi(sjd_flow *f, int j, const float *z, float *x, int batch, const sjd_jacobi_opts *opts, int *passes_out,
-               bool *nonfinite_out, hipStream_t s) {
+               bool *nonfinite_out, hipStream_t s, bool trace = false, const float *x_ref = nullptr) {
     const sjd_config &c = f->cfg;
     const int T = c.seq_len, D = c.token_dim;
     const int rev = (c.reverse_mask >> j) & 1;
@@ -317,6 +320,9 @@ int run_jacobi(sjd_flow *f, int j, const float *z, float *x, int batch, const sj
             launch_jacobi_epilogue(f->p, z, x, st, n_listed, T, D, rev, opts->tau, opts->criterion, cap,
                                    opts->drop_converged, s);
         }
+        if (trace)
+            launch_jacobi_trace(x, x_ref, st, f->trace + (size_t)passes * batch,
+                                f->trace + ((size_t)T + passes) * batch, batch, T, D, s);
         HIP_TRY(hipMemcpyAsync(f->host_pin, st.n_active_out, sizeof(int32_t), hipMemcpyDeviceToHost, s));
         HIP_TRY(hipStreamSynchronize(s));
         HIP_TRY(hipGetLastError());
@@ -514,6 +520,7 @@ int sjd_flow_create(const sjd_config *cfg, sjd_flow **out) {
     A((void **)&f->st.n_active_out, 4);
     A((void **)&f->active[0], B * 4);
     A((void **)&f->active[1], B * 4);
+    A((void **)&f->trace, 2 * T * B * 4);
     f->st.ticket = nullptr;
     A((void **)&f->t_dev, 4);
     A((void **)&f->ticket, 4);
@@ -668,6 +675,8 @@ int sjd_sample(sjd_flow *f, const float *z_dev, float *x_dev, int batch, uint32_
     const sjd_config &c = f->cfg;
     uint32_t used = c.n_blocks >= 32 ? 0xFFFFFFFFu : ((1u << c.n_blocks) - 1u);
     if ((jacobi_mask & used) && (rc = check_opts(opts))) return rc;
+    if ((jacobi_mask & used) && opts->init == 2)
+        return fail(SJD_EINVAL, "init 2 (caller's first iterate) is for single-block calls");
     hipStream_t s = (hipStream_t)hip_stream;
     HIP_TRY(hipSetDevice(f->device));
     if (stats_host) memset(stats_host, 0, sizeof(*stats_host));
@@ -702,6 +711,70 @@ int sjd_sample(sjd_flow *f, const float *z_dev, float *x_dev, int batch, uint32_
     if (stats_host)
         for (int j = 0; j < c.n_blocks; ++j) HIP_TRY(hipEventElapsedTime(&stats_host->block_ms[j], f->ev[j], f->ev[j + 1]));
     if (any_nonfinite) return fail(SJD_ENONFINITE, "a sample ended a Jacobi block with a non-finite difference norm");
+    return SJD_OK;
+}
+
+int sjd_jacobi_trace_block(sjd_flow *f, int block, const float *z_dev, float *x_dev, const float *x_ref_dev, int batch,
+                           const sjd_jacobi_opts *opts, float *delta_trace_host, float *err_trace_host,
+                           int32_t *iters_per_sample_host, int32_t *block_iters_host, void *hip_stream) {
+    int rc = check_call(f, block, z_dev, x_dev, batch);
+    if (rc) return rc;
+    if ((rc = check_opts(opts))) return rc;
+    if (!delta_trace_host) return fail(SJD_EINVAL, "null trace buffer");
+    if (err_trace_host && !x_ref_dev) return fail(SJD_EINVAL, "an error trace needs the reference solution");
+    hipStream_t s = (hipStream_t)hip_stream;
+    HIP_TRY(hipSetDevice(f->device));
+    const int T = f->cfg.seq_len;
+    int passes = 0;
+    bool nonfinite = false;
+    if ((rc = run_jacobi(f, block, z_dev, x_dev, batch, opts, &passes, &nonfinite, s, true, x_ref_dev))) return rc;
+    if (passes > 0 && batch > 0) {
+        HIP_TRY(hipMemcpyAsync(delta_trace_host, f->trace, sizeof(float) * passes * batch, hipMemcpyDeviceToHost, s));
+        if (err_trace_host)
+            HIP_TRY(hipMemcpyAsync(err_trace_host, f->trace + (size_t)T * batch, sizeof(float) * passes * batch,
+                                   hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
+    }
+    if (block_iters_host) *block_iters_host = passes;
+    if (iters_per_sample_host) memcpy(iters_per_sample_host, f->host_pin + 2, sizeof(int32_t) * batch);
+    if (nonfinite) return fail(SJD_ENONFINITE, "block %d: a sample ended with a non-finite difference norm", block);
+    return SJD_OK;
+}
+
+int sjd_forward_block(sjd_flow *f, int block, const float *x_dev, float *y_dev, float *logdet_dev, int accumulate,
+                      int batch, void *hip_stream) {
+    int rc = check_call(f, block, x_dev, y_dev, batch);
+    if (rc) return rc;
+    hipStream_t s = (hipStream_t)hip_stream;
+    HIP_TRY(hipSetDevice(f->device));
+    if (batch > 0) {
+        conditioner_pass(f, block, x_dev, batch, nullptr, s);
+        ProfScope ps(f, SJD_PROF_EPILOGUE, 0.0, (double)batch * f->cfg.seq_len * f->cfg.token_dim * 16.0, s);
+        launch_forward_epilogue(f->p, x_dev, y_dev, logdet_dev, batch, f->cfg.seq_len, f->cfg.token_dim,
+                                (f->cfg.reverse_mask >> block) & 1, accumulate ? 1 : 0, s);
+    }
+    HIP_TRY(hipStreamSynchronize(s));
+    HIP_TRY(hipGetLastError());
+    return SJD_OK;
+}
+
+int sjd_forward(sjd_flow *f, const float *x_dev, float *z_dev, float *logdet_dev, int batch, void *hip_stream) {
+    int rc = check_call(f, 0, x_dev, z_dev, batch);
+    if (rc) return rc;
+    const sjd_config &c = f->cfg;
+    hipStream_t s = (hipStream_t)hip_stream;
+    HIP_TRY(hipSetDevice(f->device));
+    const float *in = x_dev;
+    for (int j = c.n_blocks - 1; j >= 0 && batch > 0; --j) {
+        float *out = (j == 0) ? z_dev : f->pp[j & 1];
+        conditioner_pass(f, j, in, batch, nullptr, s);
+        ProfScope ps(f, SJD_PROF_EPILOGUE, 0.0, (double)batch * c.seq_len * c.token_dim * 16.0, s);
+        launch_forward_epilogue(f->p, in, out, logdet_dev, batch, c.seq_len, c.token_dim, (c.reverse_mask >> j) & 1,
+                                j != c.n_blocks - 1, s);
+        in = out;
+    }
+    HIP_TRY(hipStreamSynchronize(s));
+    HIP_TRY(hipGetLastError());
     return SJD_OK;
 }
 
