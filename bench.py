@@ -37,6 +37,14 @@ def parse():
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch (0 = as configured)")
     ap.add_argument("--seq-len", type=int, default=0, help="override the workload's token count T (0 = as configured)")
     ap.add_argument("--tau", type=float, default=0.0, help="override tau (0 = as configured)")
+    ap.add_argument("--criterion", type=int, default=0, choices=(0, 1),
+                    help="stopping norm: 0 per-sample mean |dx| (default), 1 per-sample max |dx| (Alg. 1 as printed)")
+    ap.add_argument("--init", type=int, default=0, choices=(0, 1), help="first iterate: 0 zeros, 1 the block's input")
+    ap.add_argument("--keep-converged", action="store_true",
+                    help="converged samples stay in the batch (the batch-level loop of Alg. 1) instead of leaving it")
+    ap.add_argument("--mode", default="selective", choices=("selective", "sequential", "jacobi"),
+                    help="selective: block 0 sequential, the rest Jacobi (the metric); sequential: every block "
+                         "sequential; jacobi: every block Jacobi (uniform Jacobi decoding)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-seq", action="store_true", help="skip the GPU all-sequential baseline")
     ap.add_argument("--cpu-samples", type=int, default=0, help="samples for the CPU baseline (0 = one per thread)")
@@ -69,15 +77,22 @@ def main() -> int:
         cfg = cfg.with_(seq_len=args.seq_len)
     tau = args.tau if args.tau > 0 else cfg.tau
     K = cfg.n_blocks
-    mask_sel = ~1 & ((1 << K) - 1)
+    full = (1 << K) - 1
+    how = {"selective": f"block 0 sequential, blocks 1..{K - 1} Jacobi", "sequential": "every block sequential",
+           "jacobi": "every block Jacobi"}[args.mode]
+    if args.mode != "sequential":
+        how += (", stop on max |dx|" if args.criterion else "") + (", x0 = block input" if args.init else "") + \
+               (", converged samples kept in the batch" if args.keep_converged else "")
+    mask_sel = {"selective": ~1 & full, "sequential": 0, "jacobi": full}[args.mode]
 
-    blob = wl.make_weights(cfg)
+    blob = wl.cached_weights(cfg)      # same values as make_weights(cfg), kept on disk between runs
     z_host = wl.make_latent(cfg)
     flow = sjd.Flow(cfg)
     flow.load_weights(blob)
     z = torch.from_numpy(z_host).cuda()
     x = torch.empty_like(z)
-    opts = sjd.JacobiOpts(tau=tau)
+    opts = sjd.JacobiOpts(tau=tau, criterion=args.criterion, init=args.init,
+                          drop_converged=0 if args.keep_converged else 1)
     torch.cuda.synchronize()
 
     if args.counters:
@@ -169,12 +184,12 @@ def main() -> int:
         threads = orc.num_threads()
         nb = args.cpu_samples or min(threads, cfg.batch)
         t0 = time.perf_counter()
-        rx, riters, _ = orc.sample(cfg, blob, z_host[:nb], mask_sel, tau)
+        rx, riters, _ = orc.sample(cfg, blob, z_host[:nb], mask_sel, tau, criterion=args.criterion, init=args.init)
         cdt = time.perf_counter() - t0
         gx = x[:nb].cpu().numpy()
         cpu = {"value": nb / cdt, "unit": "samples/s", "cores": min(threads, nb), "kind": "oracle",
-               "sample": f"first {nb} samples of the batch, whole cascade (block 0 sequential, blocks 1..{K - 1} "
-                         f"Jacobi, tau {tau:g}), float32 oracle, {cdt:.1f} s",
+               "sample": f"first {nb} samples of the batch, whole cascade ({how}, tau {tau:g}), float32 oracle, "
+                         f"{cdt:.1f} s",
                "max_abs_err_gpu_vs_oracle": float(np.abs(gx - rx).max()),
                "max_pass_count_difference": int(np.abs(iters[:, :nb].astype(int) - riters).max())}
 
@@ -192,9 +207,9 @@ def main() -> int:
         "dtype": "f16" if cfg.bf16 else "f32",
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: B={cfg.batch} T={cfg.seq_len} D={cfg.token_dim} K={cfg.n_blocks} "
-                               f"N={cfg.n_layers} W={cfg.width} H={cfg.n_heads}, tau={tau:g}, block 0 sequential, "
-                               f"blocks 1..{K - 1} Jacobi, seeded N(0,0.02) weights, z~N(0,{cfg.temperature:g}^2)",
-                   "batch": cfg.batch, "seq_len": cfg.seq_len, "mode": "selective"},
+                               f"N={cfg.n_layers} W={cfg.width} H={cfg.n_heads}, tau={tau:g}, {how}, "
+                               f"seeded N(0,0.02) weights, z~N(0,{cfg.temperature:g}^2)",
+                   "batch": cfg.batch, "seq_len": cfg.seq_len, "mode": args.mode},
         "jacobi_passes_per_block": stats["block_iters"],
         "mean_sample_passes_per_block": [round(v, 3) for v in stats["mean_sample_iters"]],
         "block_ms": [round(v, 3) for v in stats["block_ms"]],

@@ -53,10 +53,60 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const float *__restrict_
     for (int i = lane; i < W; i += 64) yr[i] = from_f32<OutT>((xr[i] - mean) * rstd * g[i] + b[i]);
 }
 
+// The same for widths that are multiples of 256: the row is read once, 16 bytes per lane and load,
+// and stays in registers for both statistics passes and the output (W = 256 V).
+template <typename OutT, int V>
+__global__ __launch_bounds__(256) void layernorm_vec_kernel(const float *__restrict__ x, const float *__restrict__ g,
+                                                            const float *__restrict__ b, OutT *__restrict__ y,
+                                                            int n_rows) {
+    constexpr int W = 256 * V;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (row >= n_rows) return;
+    const f32x4 *xr = reinterpret_cast<const f32x4 *>(x + (size_t)row * W);
+    f32x4 v[V];
+#pragma unroll
+    for (int k = 0; k < V; ++k) v[k] = xr[k * 64 + lane];
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < V; ++k) s += (v[k][0] + v[k][1]) + (v[k][2] + v[k][3]);
+    const float mean = wave_sum(s) / (float)W;
+    float q = 0.f;
+#pragma unroll
+    for (int k = 0; k < V; ++k)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { const float d = v[k][e] - mean; q = fmaf(d, d, q); }
+    const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)W + 1e-5f);
+    OutT *yr = y + (size_t)row * W;
+#pragma unroll
+    for (int k = 0; k < V; ++k) {
+        const f32x4 g4 = reinterpret_cast<const f32x4 *>(g)[k * 64 + lane];
+        const f32x4 b4 = reinterpret_cast<const f32x4 *>(b)[k * 64 + lane];
+        f32x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (v[k][e] - mean) * rstd * g4[e] + b4[e];
+        if constexpr (sizeof(OutT) == 4) {
+            reinterpret_cast<f32x4 *>(yr)[k * 64 + lane] = o;
+        } else {
+            typename Half16<OutT>::v4 h4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) h4[e] = from_f32<OutT>(o[e]);
+            reinterpret_cast<typename Half16<OutT>::v4 *>(yr)[k * 64 + lane] = h4;
+        }
+    }
+}
+
 template <typename OutT>
 void launch_layernorm(const float *x, const float *g, const float *b, OutT *y, int n_rows, int W, hipStream_t s) {
     if (n_rows <= 0) return;
-    hipLaunchKernelGGL(layernorm_kernel<OutT>, dim3((n_rows + 3) / 4), dim3(256), 0, s, x, g, b, y, n_rows, W);
+    const dim3 grid((n_rows + 3) / 4), block(256);
+    switch (W) {
+    case 256: hipLaunchKernelGGL((layernorm_vec_kernel<OutT, 1>), grid, block, 0, s, x, g, b, y, n_rows); break;
+    case 512: hipLaunchKernelGGL((layernorm_vec_kernel<OutT, 2>), grid, block, 0, s, x, g, b, y, n_rows); break;
+    case 768: hipLaunchKernelGGL((layernorm_vec_kernel<OutT, 3>), grid, block, 0, s, x, g, b, y, n_rows); break;
+    case 1024: hipLaunchKernelGGL((layernorm_vec_kernel<OutT, 4>), grid, block, 0, s, x, g, b, y, n_rows); break;
+    default: hipLaunchKernelGGL(layernorm_kernel<OutT>, grid, block, 0, s, x, g, b, y, n_rows, W); break;
+    }
 }
 template void launch_layernorm<float>(const float *, const float *, const float *, float *, int, int, hipStream_t);
 template void launch_layernorm<bf16>(const float *, const float *, const float *, bf16 *, int, int, hipStream_t);
