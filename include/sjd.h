@@ -99,7 +99,8 @@ typedef struct {
 #define SJD_PROF_DECODE_GEMM 3 /* projections of single-token steps */
 #define SJD_PROF_DECODE_ATTN 4 /* KV-cached single-token attention */
 #define SJD_PROF_OTHER 5       /* embedding, LayerNorm, ... */
-#define SJD_PROF_FAMILIES 6
+#define SJD_PROF_DECODE_FUSED 6 /* the sequential inverse of a whole block as one persistent kernel */
+#define SJD_PROF_FAMILIES 7
 typedef struct {
     double ms[SJD_PROF_FAMILIES];       /* summed device time per family since the last reset */
     int64_t launches[SJD_PROF_FAMILIES];
@@ -191,6 +192,13 @@ SJD_API int sjd_conditioner(sjd_flow *flow, int block, const float *x_dev, float
  * kernel: 0 chosen by shape, 1..3 a specific tile kernel.  dtype: SJD_DTYPE_BF16 or SJD_DTYPE_F16. */
 SJD_API int sjd_op_linear_h16(int dtype, int kernel, const void *a_dev, const void *wt_dev, const float *bias_dev,
                               float *resid_out_dev, void *c_dev, int M, int N, int K, int epilogue, void *hip_stream);
+
+/* How sjd_sequential_inverse_block (and the sequential blocks of sjd_sample) run in the 16-bit modes:
+ * 0 automatic (the persistent kernel where it applies, else per-step launches), 1 per-step launches
+ * replayed as a graph, 2 the persistent kernel (SJD_EINVAL at the call if the configuration is outside
+ * what it covers: head size 64, W in {256, 512, 768, 1024}, batch <= 256).  Both compute eq. 5 with the
+ * key/value cache of Sec. 3.5; they differ in how the T-1 dependent steps are scheduled on the GPU. */
+SJD_API int sjd_flow_set_sequential_path(sjd_flow *flow, int path);
 
 /* Kernel-family timing: when enabled, every launch of the selected families (bit f of
  * family_mask = SJD_PROF_* f) is bracketed by events on the caller's stream.  Costs a little time per launch. */

@@ -19,13 +19,13 @@ LIB_PATH = os.path.join(_HERE, "libsjd.so")
 SJD_OK, SJD_EINVAL, SJD_ENOMEM, SJD_EHIP, SJD_ENONFINITE, SJD_ESTATE = 0, -1, -2, -3, -4, -5
 SJD_MAX_BLOCKS = 32
 DTYPE_F32, DTYPE_BF16, DTYPE_F16 = 0, 1, 2
-PROF_GEMM, PROF_ATTENTION, PROF_EPILOGUE, PROF_DECODE_GEMM, PROF_DECODE_ATTN, PROF_OTHER = range(6)
-PROF_FAMILIES = 6
-PROF_NAMES = ("gemm", "attention", "epilogue", "decode_gemm", "decode_attn", "other")
+PROF_GEMM, PROF_ATTENTION, PROF_EPILOGUE, PROF_DECODE_GEMM, PROF_DECODE_ATTN, PROF_OTHER, PROF_DECODE_FUSED = range(7)
+PROF_FAMILIES = 7
+PROF_NAMES = ("gemm", "attention", "epilogue", "decode_gemm", "decode_attn", "other", "decode_fused")
 
 EXPORTS = ("sjd_flow_create", "sjd_flow_load_weights", "sjd_jacobi_inverse_block", "sjd_sequential_inverse_block",
            "sjd_sample", "sjd_conditioner", "sjd_op_linear_h16", "sjd_jacobi_trace_block", "sjd_forward_block",
-           "sjd_forward", "sjd_profile_enable", "sjd_profile_read", "sjd_flow_device_bytes",
+           "sjd_forward", "sjd_flow_set_sequential_path", "sjd_profile_enable", "sjd_profile_read", "sjd_flow_device_bytes",
            "sjd_last_error", "sjd_flow_destroy")
 
 
@@ -79,6 +79,7 @@ def load_library() -> C.CDLL:
                                            C.POINTER(C.c_int32), vp]
     lib.sjd_forward_block.argtypes = [vp, C.c_int, vp, vp, vp, C.c_int, C.c_int, vp]
     lib.sjd_forward.argtypes = [vp, vp, vp, vp, C.c_int, vp]
+    lib.sjd_flow_set_sequential_path.argtypes = [vp, C.c_int]
     lib.sjd_op_linear_h16.argtypes = [C.c_int, C.c_int, vp, vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, vp]
     lib.sjd_profile_enable.argtypes = [vp, C.c_uint32]
     lib.sjd_profile_read.argtypes = [vp, C.POINTER(SjdProfile), C.c_int]
@@ -269,6 +270,10 @@ class Flow:
         st = {"block_iters": list(stats.block_iters[:K]), "mean_sample_iters": list(stats.mean_sample_iters[:K]),
               "block_ms": list(stats.block_ms[:K])}
         return x, st, iters
+
+    def set_sequential_path(self, path: int) -> None:
+        """0 automatic, 1 per-step launches (graph replay), 2 persistent kernel."""
+        _check(self.lib.sjd_flow_set_sequential_path(self._h, path))
 
     def profile_enable(self, families) -> None:
         mask = 0

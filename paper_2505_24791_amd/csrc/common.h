@@ -55,6 +55,27 @@ template <> struct Half16<f16> {
     }
 };
 
+typedef float f32x4v __attribute__((ext_vector_type(4)));
+
+template <typename HT> struct Mfma16;
+template <> struct Mfma16<bf16> {
+    static __device__ __forceinline__ f32x4v run(bf16x8 a, bf16x8 b, f32x4v c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+    }
+};
+template <> struct Mfma16<f16> {
+    static __device__ __forceinline__ f32x4v run(f16x8 a, f16x8 b, f32x4v c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+    }
+};
+
+// Fragment-major layout of a [rows, K] operand of the 16x16x32 MFMA: the 64 x 8 elements one wave
+// feeds to one instruction (lane = 16*(k%32/8) + row%16 holds 8 consecutive k) are contiguous,
+// fragment (row/16, k/32) after fragment.  KS = K/32.  Returns the element index of (row, k).
+__device__ __forceinline__ size_t frag_off(int row, int k, int KS) {
+    return ((((size_t)(row >> 4) * KS + (k >> 5)) * 64 + (((k & 31) >> 3) << 4) + (row & 15)) << 3) + (k & 7);
+}
+
 __device__ __forceinline__ float gelu_erf(float v) { return 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f)); }
 
 // GELU (erf form) for results that are stored in 16 bits: erf by the rational-times-exponential
@@ -182,6 +203,32 @@ void launch_decode_epilogue(const float *p, const float *z, float *x, int B, int
                             hipStream_t s);
 
 // mu/alpha extraction for sjd_conditioner: shifted parameters in canonical order.
+// Arguments of the persistent sequential-inverse kernel (decode_persistent.hip).  All pointers are device memory.
+struct SeqLayer {
+    const float *ln1_g, *ln1_b, *b_qkv, *b_o, *ln2_g, *ln2_b, *b_fc1, *b_fc2;
+    const void *f_qkv, *f_o, *f_fc1, *f_fc2;  // fragment-major 16-bit weights
+};
+struct SeqArgs {
+    const SeqLayer *layers;
+    int n_layers, ratio;
+    const float *lnf_g, *lnf_b, *b_head;
+    const void *f_head;
+    const float *w_in, *b_in, *pos;
+    const float *z;
+    float *x;
+    float *hs;             // float32 residual stream, fragment-major, 8 groups x 16*MB rows
+    void *qkv, *o, *ff;    // 16-bit activations, fragment-major, same rows
+    float *p;              // head output, row-major [rows, 2D]
+    void *kcache, *vcache; // [layer][max_batch][T][W] 16-bit
+    size_t kv_layer_stride;  // elements between layers
+    int B, T, D, reversed;
+    int *sync;             // [0..7] members per XCD, [8] arrivals, [9] status, [64*(g+1)] barrier counter of XCD g
+    int spin_max;
+};
+size_t seq_persistent_lds_bytes(int MB, int T, int D);
+// Cooperative launch of one workgroup of 512 threads per CU (grid = number of CUs).  W = 256 S.
+hipError_t launch_seq_persistent(bool is_bf16, const SeqArgs &args, int MB, int S, int grid, hipStream_t s);
+
 void launch_jacobi_trace(const float *x, const float *x_ref, JacobiState st, float *delta_out, float *err_out, int B,
                          int T, int D, hipStream_t s);
 void launch_forward_epilogue(const float *p, const float *x, float *y, float *logdet, int B, int T, int D, int reversed,

@@ -8,20 +8,6 @@
 
 namespace sjd {
 
-typedef float f32x4v __attribute__((ext_vector_type(4)));
-
-template <typename HT> struct Mfma16;
-template <> struct Mfma16<bf16> {
-    static __device__ __forceinline__ f32x4v run(bf16x8 a, bf16x8 b, f32x4v c) {
-        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
-    }
-};
-template <> struct Mfma16<f16> {
-    static __device__ __forceinline__ f32x4v run(f16x8 a, f16x8 b, f32x4v c) {
-        return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
-    }
-};
-
 // ------------------------------------------------------------------------------------------------
 // Skinny projection C[M, N] = epi(A[M, K] * Wt[N, K]^T + bias), M <= 256.
 // 16x16x32 MFMA; both operands go straight from global memory (L2) to registers, 16 bytes per
@@ -35,9 +21,6 @@ template <> struct Mfma16<f16> {
 // MFMA (lane = 16*(k%32/8) + row%16 holds 8 consecutive k) are stored contiguously, fragment
 // (row/16, k/32) after fragment.  A wave then loads an operand fragment as one contiguous run
 // (1 KB of 16-bit data), instead of sixteen 64-byte pieces of sixteen rows.
-__device__ __forceinline__ size_t frag_off(int row, int k, int KS) {
-    return ((((size_t)(row >> 4) * KS + (k >> 5)) * 64 + (((k & 31) >> 3) << 4) + (row & 15)) << 3) + (k & 7);
-}
 
 template <typename HT, int MB, int NB, int UU, int STEP>
 __device__ __forceinline__ void skinny_group(const HT *const (&ap)[MB], const HT *const (&bp)[NB], int s,

@@ -1,0 +1,519 @@
+// Sequential inverse of one block (eq. 5 with the key/value cache of Sec. 3.5) as ONE persistent
+// kernel, for the 16-bit modes with head size 64.
+//
+// A step of the sequential inverse is a chain of ~5 N dependent skinny projections on a handful
+// of rows; launched one by one every link costs a kernel boundary (about 2 us) plus a cold start.
+// Here the chain runs inside one cooperative launch of one workgroup per CU.  The workgroups
+// that share an XCD (they share its L2) form a group; each group takes an equal share of the
+// samples and carries them through the whole block on its own, so groups never talk to each other
+// and the only synchronisation is a barrier among the ~32 workgroups of a group.  Inside a group
+// every projection is split by output columns over the members; what one member writes
+// (activations, a few KB per stage) the others read back through the shared L2:
+//   * the writer's stores are write-through; it waits for their acknowledgement (vmcnt) before it
+//     arrives at the barrier with a relaxed device-scope atomic add on the group's counter;
+//   * readers poll that counter with relaxed loads, then read the activations with loads that
+//     carry the sc1 scope bit, which never hit in the CU's own vector cache;
+//   * no L2 write-back or invalidate is needed, because writer and reader use the same L2.  (A
+//     barrier with release/acquire fences at device scope costs ~7 us for 32 members here, this
+//     one ~1 us.)
+// Weights are read-only and come through the normal cached path.  Every spin is bounded: if a
+// barrier does not complete within the spin limit the workgroup records an error and leaves, the
+// others of its group follow at their next barrier, and the host reports the failure.
+//
+// The arithmetic per row is that of the step kernels in decode.hip: LayerNorm statistics in two
+// passes over a row held in registers, 16x16x32 MFMA with K split over the 8 waves of a
+// workgroup and partial sums added in wave order, float32 residual stream.  A row's result does
+// not depend on which group or member computes it.
+#include "common.h"
+
+namespace sjd {
+
+namespace {
+
+constexpr int P_NW = 8;  // waves per workgroup
+constexpr int P_THREADS = 64 * P_NW;
+constexpr int P_CB = 4;  // 16-column blocks per round of a LayerNorm-fused projection
+constexpr int P_CBR = 2; // the same for the residual projections
+
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+
+__device__ __forceinline__ rsrc_t make_rsrc(const void *p, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
+}
+// 16-byte / 4-byte loads with the sc1 scope bit: served by L2, never by this CU's vector cache
+__device__ __forceinline__ i32x4 ld16_l2(rsrc_t rs, uint32_t byte_off) {
+    return __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, (int)byte_off, 0, 16));
+}
+__device__ __forceinline__ float ld4_l2(rsrc_t rs, uint32_t byte_off) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, (int)byte_off, 0, 16));
+}
+
+struct Ctx {
+    int tid, lane, wave, r, kg;
+    int slot, n;        // this workgroup's index in its group, members of the group
+    int rb0;            // first 16-row block of the group in the workspaces
+    int row0, nrows;    // first sample of the group, samples of the group
+    int epoch;
+    int *cnt, *status;
+    int spin_max;
+};
+
+// Barrier among the workgroups of one group (see the header).  Returns false after a time-out.
+__device__ __forceinline__ bool group_barrier(Ctx &c, volatile int *sh_ok) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's stores have been acknowledged by L2
+    __syncthreads();
+    ++c.epoch;
+    if (c.tid == 0) {
+        __hip_atomic_fetch_add(c.cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int target = c.epoch * c.n;
+        int it = 0, ok = 1;
+        while (__hip_atomic_load(c.cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+            if (++it > c.spin_max) { ok = 0; break; }
+            __builtin_amdgcn_s_sleep(1);
+        }
+        if (!ok) __hip_atomic_store(c.status, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *sh_ok = ok;
+    }
+    __syncthreads();
+    return *sh_ok != 0;
+}
+
+// C[:, cols of this member] = epi(LayerNorm(Hs) * Wt^T + bias) for the group's 16*MB workspace rows,
+// K = W = 256 S.  Hs float32 fragment-major (read through L2), Wt fragment-major, C fragment-major
+// when 16-bit, row-major [row, N] when float.  Column block cb belongs to member cb % n.
+template <typename HT, int MB, int S, int EPI, typename OutT>
+__device__ __forceinline__ void ln_gemm_stage(const Ctx &c, rsrc_t hs_rs, const float *__restrict__ g,
+                                              const float *__restrict__ be, const HT *__restrict__ Wt,
+                                              const float *__restrict__ bias, OutT *C, int N, f32x4v *red,
+                                              float *stat) {
+    typedef typename Half16<HT>::v8 v8;
+    constexpr int KS = 8 * S, W = 256 * S;
+    const int k0 = c.wave * 32 * S + c.kg * 8;
+    f32x4 xr[MB][S][2];
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            const uint32_t off = (uint32_t)((((c.rb0 + i) * KS + c.wave * S + s) * 64 + c.lane) * 8) * 4u;
+            xr[i][s][0] = __builtin_bit_cast(f32x4, ld16_l2(hs_rs, off));
+            xr[i][s][1] = __builtin_bit_cast(f32x4, ld16_l2(hs_rs, off + 16u));
+        }
+    f32x4 gr[S][2], br[S][2];
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+        gr[s][0] = *reinterpret_cast<const f32x4 *>(g + k0 + 32 * s);
+        gr[s][1] = *reinterpret_cast<const f32x4 *>(g + k0 + 32 * s + 4);
+        br[s][0] = *reinterpret_cast<const f32x4 *>(be + k0 + 32 * s);
+        br[s][1] = *reinterpret_cast<const f32x4 *>(be + k0 + 32 * s + 4);
+    }
+    // row statistics: mean, then centred sum of squares; partial sums of the 8 waves meet in LDS
+    float mean[MB], rstd[MB];
+#pragma unroll
+    for (int i = 0; i < MB; ++i) {
+        float sum = 0.f;
+#pragma unroll
+        for (int s = 0; s < S; ++s)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) sum += xr[i][s][0][e] + xr[i][s][1][e];
+        sum += __shfl_xor(sum, 16, 64);
+        sum += __shfl_xor(sum, 32, 64);
+        if (c.kg == 0) stat[c.wave * (MB * 16) + i * 16 + c.r] = sum;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < MB; ++i) {
+        float t = stat[i * 16 + c.r];
+#pragma unroll
+        for (int w = 1; w < P_NW; ++w) t += stat[w * (MB * 16) + i * 16 + c.r];
+        mean[i] = t * (1.0f / (float)W);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < MB; ++i) {
+        float m2 = 0.f;
+#pragma unroll
+        for (int s = 0; s < S; ++s)
+#pragma unroll
+            for (int h2 = 0; h2 < 2; ++h2)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { const float d = xr[i][s][h2][e] - mean[i]; m2 = fmaf(d, d, m2); }
+        m2 += __shfl_xor(m2, 16, 64);
+        m2 += __shfl_xor(m2, 32, 64);
+        if (c.kg == 0) stat[c.wave * (MB * 16) + i * 16 + c.r] = m2;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < MB; ++i) {
+        float t = stat[i * 16 + c.r];
+#pragma unroll
+        for (int w = 1; w < P_NW; ++w) t += stat[w * (MB * 16) + i * 16 + c.r];
+        rstd[i] = 1.0f / sqrtf(t * (1.0f / (float)W) + 1e-5f);
+    }
+    v8 fa[MB][S];
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int s = 0; s < S; ++s)
+#pragma unroll
+            for (int h2 = 0; h2 < 2; ++h2)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    fa[i][s][4 * h2 + e] =
+                        from_f32<HT>((xr[i][s][h2][e] - mean[i]) * rstd[i] * gr[s][h2][e] + br[s][h2][e]);
+
+    const int nbt = (N + 15) >> 4;
+    for (int cb0 = c.slot; cb0 < nbt; cb0 += P_CB * c.n) {
+        f32x4v acc[P_CB][MB];
+#pragma unroll
+        for (int cc = 0; cc < P_CB; ++cc)
+#pragma unroll
+            for (int i = 0; i < MB; ++i) acc[cc][i] = f32x4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int cc = 0; cc < P_CB; ++cc) {
+            const int cb = cb0 + cc * c.n;
+            if (cb < nbt) {
+#pragma unroll
+                for (int s = 0; s < S; ++s) {
+                    const v8 fb =
+                        *reinterpret_cast<const v8 *>(Wt + (((size_t)cb * KS + c.wave * S + s) * 64 + c.lane) * 8);
+#pragma unroll
+                    for (int i = 0; i < MB; ++i) acc[cc][i] = Mfma16<HT>::run(fa[i][s], fb, acc[cc][i]);
+                }
+            }
+        }
+#pragma unroll
+        for (int cc = 0; cc < P_CB; ++cc)
+#pragma unroll
+            for (int i = 0; i < MB; ++i) red[(c.wave * (P_CB * MB) + cc * MB + i) * 64 + c.lane] = acc[cc][i];
+        __syncthreads();
+        // output block q = (cc, i) is summed in wave order and finished by wave q % 8
+        for (int q = c.wave; q < P_CB * MB; q += P_NW) {
+            const int cc = q / MB, i = q % MB;
+            const int cb = cb0 + cc * c.n;
+            const int col = cb * 16 + c.r;
+            if (cb < nbt && col < N) {
+                f32x4v t = red[q * 64 + c.lane];
+#pragma unroll
+                for (int w = 1; w < P_NW; ++w) t += red[(w * (P_CB * MB) + q) * 64 + c.lane];
+                const float bv = bias[col];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int row = (c.rb0 + i) * 16 + 4 * c.kg + v;
+                    float val = t[v] + bv;
+                    if (EPI == EPI_BIAS_GELU) val = gelu_erf_h16(val);
+                    if constexpr (sizeof(OutT) == 2) C[frag_off(row, col, N >> 5)] = from_f32<OutT>(val);
+                    else C[(size_t)row * N + col] = val;
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// Hs[:, cols of this member] += A * Wt^T + bias for the group's rows; N = W = 256 S, K = kmul * W.
+// A 16-bit fragment-major (read through L2), Hs float32 fragment-major (read through L2, written).
+template <typename HT, int MB, int S>
+__device__ __forceinline__ void gemm_resid_stage(const Ctx &c, rsrc_t a_rs, int kmul, const HT *__restrict__ Wt,
+                                                 const float *__restrict__ bias, rsrc_t hs_rs, float *hs,
+                                                 f32x4v *red) {
+    typedef typename Half16<HT>::v8 v8;
+    constexpr int W = 256 * S, KSN = W / 32;
+    const int KSA = 8 * S * kmul;  // k-steps of the whole K
+    const int ksw = S * kmul;      // k-steps of one wave
+    constexpr int nbt = W / 16;
+    for (int cb0 = c.slot; cb0 < nbt; cb0 += P_CBR * c.n) {
+        f32x4v acc[P_CBR][MB];
+#pragma unroll
+        for (int cc = 0; cc < P_CBR; ++cc)
+#pragma unroll
+            for (int i = 0; i < MB; ++i) acc[cc][i] = f32x4v{0.f, 0.f, 0.f, 0.f};
+        for (int ch = 0; ch < kmul; ++ch) {
+            const int ks0 = c.wave * ksw + ch * S;
+            v8 fa[MB][S];
+#pragma unroll
+            for (int i = 0; i < MB; ++i)
+#pragma unroll
+                for (int u = 0; u < S; ++u) {
+                    const uint32_t off = (uint32_t)((((c.rb0 + i) * KSA + ks0 + u) * 64 + c.lane) * 8) * 2u;
+                    fa[i][u] = __builtin_bit_cast(v8, ld16_l2(a_rs, off));
+                }
+#pragma unroll
+            for (int cc = 0; cc < P_CBR; ++cc) {
+                const int cb = cb0 + cc * c.n;
+                if (cb < nbt) {
+#pragma unroll
+                    for (int u = 0; u < S; ++u) {
+                        const v8 fb =
+                            *reinterpret_cast<const v8 *>(Wt + (((size_t)cb * KSA + ks0 + u) * 64 + c.lane) * 8);
+#pragma unroll
+                        for (int i = 0; i < MB; ++i) acc[cc][i] = Mfma16<HT>::run(fa[i][u], fb, acc[cc][i]);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int cc = 0; cc < P_CBR; ++cc)
+#pragma unroll
+            for (int i = 0; i < MB; ++i) red[(c.wave * (P_CBR * MB) + cc * MB + i) * 64 + c.lane] = acc[cc][i];
+        __syncthreads();
+        for (int q = c.wave; q < P_CBR * MB; q += P_NW) {
+            const int cc = q / MB, i = q % MB;
+            const int cb = cb0 + cc * c.n;
+            if (cb < nbt) {
+                const int col = cb * 16 + c.r;
+                float rv[4];
+                size_t eo[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    eo[v] = frag_off((c.rb0 + i) * 16 + 4 * c.kg + v, col, KSN);
+                    rv[v] = ld4_l2(hs_rs, (uint32_t)eo[v] * 4u);
+                }
+                f32x4v t = red[q * 64 + c.lane];
+#pragma unroll
+                for (int w = 1; w < P_NW; ++w) t += red[(w * (P_CBR * MB) + q) * 64 + c.lane];
+                const float bv = bias[col];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) hs[eo[v]] = (t[v] + bv) + rv[v];
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// Single-token attention of the group's (sample, head) pairs against the cache at position t:
+// pair (row, h) belongs to member (row * H + h) % n.  The workgroup's 512 threads are 64 key
+// groups x 8 sixteen-byte chunks of the head.  This step's k and v are appended to the cache.
+template <typename HT, int S>
+__device__ __forceinline__ void attention_stage(const Ctx &c, rsrc_t qkv_rs, HT *kc, HT *vc, rsrc_t kc_rs, rsrc_t vc_rs,
+                                                HT *o, int t, int T, float *sc, float *opart, float *wred) {
+    typedef typename Half16<HT>::v8 v8;
+    constexpr int W = 256 * S, H = W / 64, KS3 = 3 * W / 32;
+    const int dc = c.tid & 7, sg = c.tid >> 3;
+    const int npairs = c.nrows * H;
+    for (int pi = c.slot; pi < npairs; pi += c.n) {
+        const int row = pi / H, h = pi - row * H;
+        const int b = c.row0 + row, wsrow = c.rb0 * 16 + row;
+        auto chunk = [&](int part, int ci) -> v8 {
+            return __builtin_bit_cast(v8, ld16_l2(qkv_rs, (uint32_t)frag_off(wsrow, part * W + h * 64 + ci * 8, KS3) * 2u));
+        };
+        const v8 kfresh = chunk(1, dc), vfresh = chunk(2, dc);
+        const size_t cbase = ((size_t)b * T) * W + h * 64;
+        if (c.tid < 8) *reinterpret_cast<v8 *>(kc + cbase + (size_t)t * W + c.tid * 8) = chunk(1, c.tid);
+        else if (c.tid < 16) *reinterpret_cast<v8 *>(vc + cbase + (size_t)t * W + (c.tid - 8) * 8) = chunk(2, c.tid - 8);
+        float qf[8];
+        {
+            const v8 q8 = chunk(0, dc);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) qf[e] = (float)q8[e] * 0.125f;  // 1/sqrt(64)
+        }
+        const int nk = t + 1;
+        float mx = -INFINITY;
+        for (int s = sg; s < nk; s += 64) {
+            const v8 k8 = s < t ? __builtin_bit_cast(v8, ld16_l2(kc_rs, (uint32_t)(cbase + (size_t)s * W + dc * 8) * 2u))
+                                : kfresh;
+            float d = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) d = fmaf(qf[e], (float)k8[e], d);
+            d += __shfl_xor(d, 1, 64);
+            d += __shfl_xor(d, 2, 64);
+            d += __shfl_xor(d, 4, 64);
+            if (dc == 0) sc[s] = d;
+            mx = fmaxf(mx, d);
+        }
+        mx = wave_max(mx);
+        if (c.lane == 0) wred[c.wave] = mx;
+        __syncthreads();
+        mx = wred[0];
+#pragma unroll
+        for (int w = 1; w < P_NW; ++w) mx = fmaxf(mx, wred[w]);
+        float acc[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+        float psum = 0.f;
+        for (int s = sg; s < nk; s += 64) {
+            const float p = expf(sc[s] - mx);
+            const v8 v8v = s < t ? __builtin_bit_cast(v8, ld16_l2(vc_rs, (uint32_t)(cbase + (size_t)s * W + dc * 8) * 2u))
+                                 : vfresh;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] = fmaf(p, (float)v8v[e], acc[e]);
+            psum += p;
+        }
+        // the 8 key groups of a wave (lanes differing in bits 3..5), then the 8 waves in index order
+#pragma unroll
+        for (int off = 8; off < 64; off <<= 1) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] += __shfl_xor(acc[e], off, 64);
+            psum += __shfl_xor(psum, off, 64);
+        }
+        if (c.lane < 8) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) opart[c.wave * 64 + c.lane * 8 + e] = acc[e];
+            if (c.lane == 0) wred[P_NW + c.wave] = psum;
+        }
+        __syncthreads();
+        if (c.tid < 8) {
+            float den = wred[P_NW];
+#pragma unroll
+            for (int w = 1; w < P_NW; ++w) den += wred[P_NW + w];
+            v8 ov;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int d = c.tid * 8 + e;
+                float sum = opart[d];
+#pragma unroll
+                for (int w = 1; w < P_NW; ++w) sum += opart[w * 64 + d];
+                ov[e] = from_f32<HT>(sum / den);
+            }
+            *reinterpret_cast<v8 *>(o + frag_off(wsrow, h * 64 + c.tid * 8, W / 32)) = ov;
+        }
+        __syncthreads();  // sc, opart and wred are reused by the next pair
+    }
+}
+
+template <typename HT, int MB, int S>
+__global__ __launch_bounds__(P_THREADS) void seq_persistent_kernel(SeqArgs a) {
+    constexpr int W = 256 * S, RW_ROWS = 16 * MB;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    __shared__ int sh[8];
+    f32x4v *red = reinterpret_cast<f32x4v *>(lds_raw);                       // [8][P_CB*MB][64]
+    float *stat = reinterpret_cast<float *>(lds_raw + (size_t)P_NW * P_CB * MB * 64 * 16);  // [8][MB*16]
+    float *xs = stat + P_NW * MB * 16;                                        // [16*MB][D]
+    float *opart = xs + RW_ROWS * a.D;                                        // [8][64]
+    float *wred = opart + P_NW * 64;                                          // [16]
+    float *sc = wred + 16;                                                    // [T]
+
+    Ctx c;
+    c.tid = threadIdx.x; c.lane = c.tid & 63; c.wave = c.tid >> 6; c.r = c.lane & 15; c.kg = c.lane >> 4;
+    c.epoch = 0; c.status = a.sync + 9; c.spin_max = a.spin_max;
+
+    // ---- groups: the workgroups of one XCD, found from the hardware's XCC id
+    if (c.tid == 0) {
+        const int xcc = __builtin_amdgcn_s_getreg(20 | (3 << 11)) & 7;  // HW_REG_XCC_ID, bits 3:0
+        const int slot = atomicAdd(&a.sync[xcc], 1);
+        atomicAdd(&a.sync[8], 1);
+        int it = 0, ok = 1;
+        while (__hip_atomic_load(&a.sync[8], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < (int)gridDim.x) {
+            if (++it > a.spin_max) { ok = 0; break; }
+            __builtin_amdgcn_s_sleep(2);
+        }
+        int n = 0, groups = 0, gidx = 0;
+        for (int g = 0; g < 8; ++g) {
+            const int m = __hip_atomic_load(&a.sync[g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (m > 0) { if (g < xcc) ++gidx; ++groups; }
+            if (g == xcc) n = m;
+        }
+        if (!ok) __hip_atomic_store(c.status, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sh[0] = ok; sh[1] = slot; sh[2] = n; sh[3] = groups; sh[4] = gidx; sh[5] = xcc;
+    }
+    __syncthreads();
+    if (!sh[0]) return;
+    c.slot = sh[1]; c.n = sh[2];
+    const int groups = sh[3], gidx = sh[4];
+    c.cnt = a.sync + 64 * (sh[5] + 1);
+    const int per = (a.B + groups - 1) / groups;  // samples per group
+    if (per > RW_ROWS) {                           // fewer groups than the host planned for
+        if (c.tid == 0) __hip_atomic_store(c.status, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return;
+    }
+    c.row0 = gidx * per;
+    c.nrows = a.B - c.row0 < per ? a.B - c.row0 : per;
+    c.rb0 = gidx * MB;
+    if (c.nrows <= 0) return;                      // groups are independent: an idle one just leaves
+
+    const int T = a.T, D = a.D;
+    HT *qkv = reinterpret_cast<HT *>(a.qkv), *o = reinterpret_cast<HT *>(a.o), *ff = reinterpret_cast<HT *>(a.ff);
+    const uint32_t ws_rows = 8u * RW_ROWS;
+    const rsrc_t hs_rs = make_rsrc(a.hs, ws_rows * W * 4u);
+    const rsrc_t qkv_rs = make_rsrc(qkv, ws_rows * 3u * W * 2u);
+    const rsrc_t o_rs = make_rsrc(o, ws_rows * W * 2u);
+    const rsrc_t ff_rs = make_rsrc(ff, ws_rows * (uint32_t)a.ratio * W * 2u);
+    const rsrc_t p_rs = make_rsrc(a.p, ws_rows * 2u * D * 4u);
+    volatile int *sh_ok = &sh[6];
+
+    for (int l = 0; l < T; ++l) {
+        // ---- x_l of the group's samples (eq. 5; x_0 = z_0), kept in LDS for the embedding
+        const int tok = a.reversed ? T - 1 - l : l;
+        for (int e = c.tid; e < RW_ROWS * D; e += P_THREADS) {
+            const int row = e / D, d = e - row * D;
+            float xn = 0.f;
+            if (row < c.nrows) {
+                const size_t idx = ((size_t)(c.row0 + row) * T + tok) * D + d;
+                xn = a.z[idx];
+                if (l > 0) {
+                    const uint32_t po = (uint32_t)((c.rb0 * 16 + row) * 2 * D + d) * 4u;
+                    xn = fmaf(xn, expf(ld4_l2(p_rs, po + (uint32_t)D * 4u)), ld4_l2(p_rs, po));
+                }
+                if (c.slot == 0) a.x[idx] = xn;
+            }
+            xs[e] = xn;
+        }
+        if (l == T - 1) break;
+        __syncthreads();
+        // ---- embedding of this member's column blocks: hs = x_l * w_in + b_in + pos[l]
+        for (int cb = c.slot; cb < W / 16; cb += c.n) {
+            for (int e = c.tid; e < RW_ROWS * 16; e += P_THREADS) {
+                const int row = e >> 4, col = cb * 16 + (e & 15);
+                float acc = a.b_in[col] + a.pos[(size_t)l * W + col];
+                for (int d = 0; d < D; ++d) acc = fmaf(xs[row * D + d], a.w_in[(size_t)d * W + col], acc);
+                a.hs[frag_off(c.rb0 * 16 + row, col, W / 32)] = acc;
+            }
+        }
+        if (!group_barrier(c, sh_ok)) return;
+
+        for (int ly = 0; ly < a.n_layers; ++ly) {
+            const SeqLayer &lw = a.layers[ly];
+            HT *kc = reinterpret_cast<HT *>(a.kcache) + (size_t)ly * a.kv_layer_stride;
+            HT *vc = reinterpret_cast<HT *>(a.vcache) + (size_t)ly * a.kv_layer_stride;
+            const rsrc_t kc_rs = make_rsrc(kc, (uint32_t)(a.kv_layer_stride * 2u));
+            const rsrc_t vc_rs = make_rsrc(vc, (uint32_t)(a.kv_layer_stride * 2u));
+            ln_gemm_stage<HT, MB, S, EPI_BIAS, HT>(c, hs_rs, lw.ln1_g, lw.ln1_b, (const HT *)lw.f_qkv, lw.b_qkv, qkv,
+                                                  3 * W, red, stat);
+            if (!group_barrier(c, sh_ok)) return;
+            attention_stage<HT, S>(c, qkv_rs, kc, vc, kc_rs, vc_rs, o, l, T, sc, opart, wred);
+            if (!group_barrier(c, sh_ok)) return;
+            gemm_resid_stage<HT, MB, S>(c, o_rs, 1, (const HT *)lw.f_o, lw.b_o, hs_rs, a.hs, red);
+            if (!group_barrier(c, sh_ok)) return;
+            ln_gemm_stage<HT, MB, S, EPI_BIAS_GELU, HT>(c, hs_rs, lw.ln2_g, lw.ln2_b, (const HT *)lw.f_fc1, lw.b_fc1, ff,
+                                                       a.ratio * W, red, stat);
+            if (!group_barrier(c, sh_ok)) return;
+            gemm_resid_stage<HT, MB, S>(c, ff_rs, a.ratio, (const HT *)lw.f_fc2, lw.b_fc2, hs_rs, a.hs, red);
+            if (!group_barrier(c, sh_ok)) return;
+        }
+        ln_gemm_stage<HT, MB, S, EPI_BIAS, float>(c, hs_rs, a.lnf_g, a.lnf_b, (const HT *)a.f_head, a.b_head, a.p, 2 * D,
+                                                 red, stat);
+        if (!group_barrier(c, sh_ok)) return;
+    }
+}
+
+}  // namespace
+
+size_t seq_persistent_lds_bytes(int MB, int T, int D) {
+    size_t need = (size_t)P_NW * P_CB * MB * 64 * 16 + (size_t)P_NW * MB * 16 * 4 + (size_t)16 * MB * D * 4 +
+                  (size_t)P_NW * 64 * 4 + 16 * 4 + (size_t)T * 4;
+    const size_t one_per_cu = 84 * 1024;  // more than half of a CU's LDS: exactly one workgroup per CU
+    if (need < one_per_cu) need = one_per_cu;
+    return (need + 255) & ~(size_t)255;
+}
+
+template <typename HT>
+static const void *pick_kernel(int MB, int S) {
+#define SJD_PK(MBv, Sv) if (MB == MBv && S == Sv) return reinterpret_cast<const void *>(&seq_persistent_kernel<HT, MBv, Sv>);
+    SJD_PK(1, 1) SJD_PK(1, 2) SJD_PK(1, 3) SJD_PK(1, 4) SJD_PK(2, 1) SJD_PK(2, 2) SJD_PK(2, 3) SJD_PK(2, 4)
+#undef SJD_PK
+    return nullptr;
+}
+
+hipError_t launch_seq_persistent(bool is_bf16, const SeqArgs &args, int MB, int S, int grid, hipStream_t s) {
+    const void *kern = is_bf16 ? pick_kernel<bf16>(MB, S) : pick_kernel<f16>(MB, S);
+    if (!kern) return hipErrorInvalidValue;
+    const size_t lds = seq_persistent_lds_bytes(MB, args.T, args.D);
+    hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    SeqArgs a = args;
+    void *params[] = {&a};
+    return hipLaunchCooperativeKernel(kern, dim3(grid), dim3(P_THREADS), params, (unsigned)lds, s);
+}
+
+}  // namespace sjd

@@ -46,6 +46,7 @@ struct BlockW {
     const float *w_in, *b_in, *pos, *lnf_g, *lnf_b, *w_head, *b_head;
     void *t_head, *f_head;
     std::vector<LayerW> layer;
+    SeqLayer *seq_layers = nullptr;   // device copy of the per-layer pointers for the persistent sequential kernel
 };
 
 struct ProfSpan { hipEvent_t a, b; int fam; };
@@ -77,6 +78,10 @@ struct sjd_flow {
     hipStream_t cap_stream = nullptr;
     std::map<std::tuple<int, int, const void *, const void *>, hipGraphExec_t> step_graphs;
     int use_graphs = 1;
+    int seq_path = 0;            // 0 automatic, 1 per-step launches (graph replay), 2 persistent kernel
+    int *psync = nullptr;        // synchronisation words of the persistent kernel (1024 ints)
+    SeqLayer *seq_layers = nullptr;  // [n_blocks][n_layers] on the device
+    int n_cus = 0, coop = 0;
     hipEvent_t ev[SJD_MAX_BLOCKS + 1] = {};
     // profiling
     uint32_t prof_mask = 0;
@@ -449,10 +454,55 @@ int run_sequential_fast(sjd_flow *f, int j, const float *z, float *x, int batch,
     return SJD_OK;
 }
 
+// The persistent kernel covers: 16-bit modes, head size 64, W in {256, 512, 768, 1024}, batch <= 256,
+// a cooperative launch of one workgroup per CU, and per-layer caches below 4 GiB (32-bit offsets).
+bool persistent_ok(const sjd_flow *f, int batch) {
+    const sjd_config &c = f->cfg;
+    return frag_ok(f, batch) && f->coop && f->n_cus >= 8 && batch <= 256 && c.token_dim <= 256 &&
+           (size_t)c.max_batch * c.seq_len * c.width * 2 < ((size_t)1 << 32) &&
+           seq_persistent_lds_bytes(batch <= 128 ? 1 : 2, c.seq_len, c.token_dim) <= 160 * 1024;
+}
+
+int run_sequential_persistent(sjd_flow *f, int j, const float *z, float *x, int batch, hipStream_t s) {
+    const sjd_config &c = f->cfg;
+    const BlockW &bw = f->block[j];
+    const int MB = batch <= 128 ? 1 : 2;
+    SeqArgs a{};
+    a.layers = bw.seq_layers; a.n_layers = c.n_layers; a.ratio = c.mlp_ratio;
+    a.lnf_g = bw.lnf_g; a.lnf_b = bw.lnf_b; a.b_head = bw.b_head; a.f_head = bw.f_head;
+    a.w_in = bw.w_in; a.b_in = bw.b_in; a.pos = bw.pos;
+    a.z = z; a.x = x;
+    a.hs = f->h; a.qkv = f->qkv; a.o = f->o; a.ff = f->f; a.p = f->p;
+    a.kcache = f->kcache; a.vcache = f->vcache;
+    a.kv_layer_stride = (size_t)c.max_batch * c.seq_len * c.width;
+    a.B = batch; a.T = c.seq_len; a.D = c.token_dim; a.reversed = (c.reverse_mask >> j) & 1;
+    a.sync = f->psync;
+    a.spin_max = 1 << 21;  // a poll takes ~0.5 us: about a second before a barrier gives up
+    const double steps = c.seq_len - 1.0, W = c.width, R = c.mlp_ratio;
+    const double wbytes = c.n_layers * (4.0 + 2.0 * R) * W * W * 2.0 + 2.0 * c.token_dim * W * 2.0;
+    const double kvbytes = (double)c.n_layers * batch * (c.seq_len / 2.0) * W * 2.0 * 2.0;
+    ProfScope ps(f, SJD_PROF_DECODE_FUSED, steps * 2.0 * batch * (c.n_layers * (4.0 + 2.0 * R) * W * W + 2.0 * c.token_dim * W) +
+                                               steps * 4.0 * batch * (c.seq_len / 2.0) * W * c.n_layers,
+                 steps * (wbytes + kvbytes), s);
+    HIP_TRY(hipMemsetAsync(f->psync, 0, 1024 * sizeof(int), s));
+    hipError_t e = launch_seq_persistent(c.dtype == SJD_DTYPE_BF16, a, MB, c.width / 256, f->n_cus, s);
+    if (e != hipSuccess) return fail(SJD_EHIP, "persistent sequential kernel: launch failed: %s", hipGetErrorString(e));
+    HIP_TRY(hipMemcpyAsync(f->host_pin, f->psync + 9, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    HIP_TRY(hipGetLastError());
+    if (f->host_pin[0] != 0)
+        return fail(SJD_EHIP, "persistent sequential kernel: %s",
+                    f->host_pin[0] == 2 ? "fewer XCD groups than planned for" : "a group barrier timed out");
+    return SJD_OK;
+}
+
 int run_sequential(sjd_flow *f, int j, const float *z, float *x, int batch, hipStream_t s) {
     const int T = f->cfg.seq_len, D = f->cfg.token_dim;
     const int rev = (f->cfg.reverse_mask >> j) & 1;
     if (batch == 0) return SJD_OK;
+    if (f->seq_path == 2 && !persistent_ok(f, batch))
+        return fail(SJD_EINVAL, "the persistent sequential kernel does not cover this configuration");
+    if (f->seq_path != 1 && persistent_ok(f, batch)) return run_sequential_persistent(f, j, z, x, batch, s);
     if (fast_decode_ok(f)) return run_sequential_fast(f, j, z, x, batch, s);
     launch_decode_epilogue(f->p, z, x, batch, T, D, -1, rev, s);  // x_1 = y_1
     for (int t = 0; t + 1 < T; ++t) decode_step(f, j, z, x, batch, t, s);
@@ -497,7 +547,7 @@ int sjd_flow_create(const sjd_config *cfg, sjd_flow **out) {
     f->cfg = c;
     f->device = dev;
     const size_t T = c.seq_len, W = c.width, D = c.token_dim, R = c.mlp_ratio, B = c.max_batch, N = c.n_layers;
-    const size_t M = B * T > 64 ? B * T : 64, ab = act_bytes(f);  // single-token kernels work on 64-row tiles
+    const size_t M = B * T > 256 ? B * T : 256, ab = act_bytes(f);  // the single-token paths work on up to 8 x 32 rows
     int rc = SJD_OK;
     auto A = [&](void **p, size_t n) { if (rc == SJD_OK) rc = dev_alloc(f, p, n); };
     A((void **)&f->blob, (size_t)c.n_blocks * block_floats(c) * sizeof(float));
@@ -521,6 +571,15 @@ int sjd_flow_create(const sjd_config *cfg, sjd_flow **out) {
     A((void **)&f->active[0], B * 4);
     A((void **)&f->active[1], B * 4);
     A((void **)&f->trace, 2 * T * B * 4);
+    A((void **)&f->psync, 1024 * sizeof(int));
+    A((void **)&f->seq_layers, (size_t)c.n_blocks * N * sizeof(SeqLayer));
+    {
+        hipDeviceProp_t prop;
+        if (rc == SJD_OK && hipGetDeviceProperties(&prop, f->device) == hipSuccess) {
+            f->n_cus = prop.multiProcessorCount;
+            f->coop = prop.cooperativeLaunch;
+        }
+    }
     f->st.ticket = nullptr;
     A((void **)&f->t_dev, 4);
     A((void **)&f->ticket, 4);
@@ -617,6 +676,14 @@ int sjd_flow_load_weights(sjd_flow *f, const void *host_blob, size_t nbytes) {
         bw.b_head = p;
         bw.t_head = prep(bw.w_head, W, 2 * D);
         bw.f_head = prep_frag(bw.w_head, W, 2 * D);
+        std::vector<SeqLayer> sl(c.n_layers);
+        for (int l = 0; l < c.n_layers; ++l) {
+            const LayerW &lw = bw.layer[l];
+            sl[l] = SeqLayer{lw.ln1_g, lw.ln1_b, lw.b_qkv, lw.b_o, lw.ln2_g, lw.ln2_b, lw.b_fc1, lw.b_fc2,
+                             lw.f_qkv, lw.f_o, lw.f_fc1, lw.f_fc2};
+        }
+        bw.seq_layers = f->seq_layers + (size_t)j * c.n_layers;
+        HIP_TRY(hipMemcpy(bw.seq_layers, sl.data(), sl.size() * sizeof(SeqLayer), hipMemcpyHostToDevice));
     }
     HIP_TRY(hipDeviceSynchronize());
     HIP_TRY(hipGetLastError());
@@ -797,6 +864,13 @@ int sjd_op_linear_h16(int dtype, int kernel, const void *a_dev, const void *wt_d
     }
     HIP_TRY(hipStreamSynchronize(s));
     HIP_TRY(hipGetLastError());
+    return SJD_OK;
+}
+
+int sjd_flow_set_sequential_path(sjd_flow *f, int path) {
+    if (!f) return fail(SJD_EINVAL, "null flow");
+    if (path < 0 || path > 2) return fail(SJD_EINVAL, "path must be 0 (automatic), 1 (per-step launches) or 2 (persistent kernel)");
+    f->seq_path = path;
     return SJD_OK;
 }
 

@@ -160,6 +160,7 @@ def test_two_runs_are_bitwise_identical_and_graph_replay_equals_eager(torch_cuda
     torch = torch_cuda
     cfg = SMALL_H16
     f, _ = _make(cfg)
+    f.set_sequential_path(1)                             # per-step launches, replayed as a graph
     zd = _dev(torch, wl.make_latent(cfg))
     sel = ~1 & ((1 << cfg.n_blocks) - 1)
     a, _, ia = f.sample(zd, sel, sjd.JacobiOpts(tau=cfg.tau))
@@ -178,6 +179,16 @@ def test_two_runs_are_bitwise_identical_and_graph_replay_equals_eager(torch_cuda
     z2 = zd[:5].clone()
     d, _, _ = f.sample(z2, sel, sjd.JacobiOpts(tau=cfg.tau))
     assert torch.equal(d, a[:5])
+    # the persistent kernel: also the same bits run after run, with and without kernel timing
+    f.set_sequential_path(2)
+    p1, _, ip1 = f.sample(zd, sel, sjd.JacobiOpts(tau=cfg.tau))
+    f.profile_enable(range(sjd.PROF_FAMILIES))
+    p2, _, ip2 = f.sample(zd, sel, sjd.JacobiOpts(tau=cfg.tau))
+    prof = f.profile_read()
+    f.profile_enable([])
+    assert torch.equal(p1, p2) and np.array_equal(ip1, ip2)
+    assert prof["decode_fused"]["launches"] == 1 and prof["decode_gemm"]["launches"] == 0
+    assert (p1 - a).abs().max().item() <= 2e-2
     f.close()
 
 

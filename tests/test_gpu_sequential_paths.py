@@ -1,0 +1,80 @@
+"""The two schedules of the sequential inverse in the 16-bit modes (per-step launches and the
+persistent kernel) against the CPU oracle and against each other, through the C boundary.
+Needs an MI355X.  Tolerance: 2e-2 on the block's output (the 16-bit bound of this build)."""
+import numpy as np
+import pytest
+
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+
+CASES = [
+    # name, config: widths 256 S for S = 1..4, batches that give ragged groups (B not a multiple of 8),
+    # a batch above 128 (two row blocks per group), one sample, a reversed block
+    ("w256_b5", wl.FlowConfig("w256_b5", n_blocks=2, n_layers=2, width=256, n_heads=4, seq_len=40, token_dim=6, batch=5, bf16=True)),
+    ("w512_b64", wl.FlowConfig("w512_b64", n_blocks=2, n_layers=2, width=512, n_heads=8, seq_len=33, token_dim=12, batch=64, bf16=True)),
+    ("w768_b19", wl.FlowConfig("w768_b19", n_blocks=2, n_layers=1, width=768, n_heads=12, seq_len=20, token_dim=12, batch=19, bf16=True)),
+    ("w1024_b9", wl.FlowConfig("w1024_b9", n_blocks=2, n_layers=1, width=1024, n_heads=16, seq_len=18, token_dim=48, batch=9, bf16=True)),
+    ("w256_b150", wl.FlowConfig("w256_b150", n_blocks=2, n_layers=1, width=256, n_heads=4, seq_len=12, token_dim=4, batch=150, bf16=True)),
+    ("w256_b1", wl.FlowConfig("w256_b1", n_blocks=2, n_layers=2, width=256, n_heads=4, seq_len=70, token_dim=3, batch=1, bf16=True)),
+]
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return torch
+
+
+@pytest.mark.parametrize("name,cfg", CASES, ids=[c[0] for c in CASES])
+@pytest.mark.parametrize("dtype_name", ["f16", "bf16"])
+def test_sequential_paths_match_oracle(torch_cuda, orc32, name, cfg, dtype_name):
+    import paper_2505_24791_amd as sjd
+    torch = torch_cuda
+    print(f"case {name} {dtype_name}", flush=True)
+    dtype = sjd.DTYPE_F16 if dtype_name == "f16" else sjd.DTYPE_BF16
+    blob = wl.make_weights(cfg, perturb_affine=True)
+    z = wl.make_latent(cfg, seed=41)
+    zd = torch.from_numpy(z).cuda()
+    f = sjd.Flow(cfg, dtype=dtype)
+    f.load_weights(blob)
+    tol = TOL if dtype_name == "f16" else 4 * TOL      # bf16 operands: 8 mantissa bits (kept for coverage)
+    for j in range(cfg.n_blocks):                      # block 1 works on the reversed token order
+        outs = {}
+        for path in (1, 2):
+            f.set_sequential_path(path)
+            outs[path] = f.sequential_inverse_block(j, zd).cpu().numpy()
+            again = f.sequential_inverse_block(j, zd).cpu().numpy()
+            assert np.array_equal(outs[path], again), (path, "not deterministic")
+        ref = np.stack([orc32.sequential_inverse_block(cfg, blob, j, z[b]) for b in range(min(cfg.batch, 12))])
+        nb = ref.shape[0]
+        for path in (1, 2):
+            assert np.isfinite(outs[path]).all()
+            assert np.abs(outs[path][:nb] - ref).max() <= tol, (j, path)
+        assert np.abs(outs[1] - outs[2]).max() <= tol, j
+        # samples are independent: the last sample alone gives the same bits as inside the batch
+        if cfg.batch > 1:
+            f.set_sequential_path(2)
+            one = f.sequential_inverse_block(j, zd[-1:].contiguous()).cpu().numpy()
+            assert np.array_equal(one[0], outs[2][-1])
+    f.close()
+
+
+def test_persistent_path_is_refused_outside_its_coverage(torch_cuda):
+    import paper_2505_24791_amd as sjd
+    torch = torch_cuda
+    cfg = wl.FlowConfig("dh32", n_blocks=1, n_layers=1, width=128, n_heads=4, seq_len=8, token_dim=4, batch=2, bf16=True)
+    f = sjd.Flow(cfg)
+    f.load_weights(wl.make_weights(cfg))
+    z = torch.from_numpy(wl.make_latent(cfg)).cuda()
+    f.set_sequential_path(2)
+    with pytest.raises(sjd.SjdError) as e:
+        f.sequential_inverse_block(0, z)
+    assert e.value.code == sjd.SJD_EINVAL
+    f.set_sequential_path(0)
+    assert torch.isfinite(f.sequential_inverse_block(0, z)).all()
+    with pytest.raises(sjd.SjdError):
+        f.set_sequential_path(3)
+    f.close()
