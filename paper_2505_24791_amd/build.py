@@ -38,7 +38,8 @@ def build(verbose: bool = False) -> str:
     os.makedirs(os.path.join(HERE, "_build"), exist_ok=True)
     for src in sources():
         obj = os.path.join(HERE, "_build", os.path.basename(src) + ".o")
-        cmd = [hipcc, *[f for f in HIPCC_FLAGS if f != "-shared"], "-c", src, "-o", obj]
+        extra = os.environ.get("SJD_EXTRA_FLAGS", "").split()          # e.g. -DSJD_SEQ_TIMELINE for development builds
+        cmd = [hipcc, *[f for f in HIPCC_FLAGS if f != "-shared"], *extra, "-c", src, "-o", obj]
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         objs.append(obj)
     for src, p in procs:

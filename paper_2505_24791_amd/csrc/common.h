@@ -208,8 +208,9 @@ struct SeqLayer {
     const float *ln1_g, *ln1_b, *b_qkv, *b_o, *ln2_g, *ln2_b, *b_fc1, *b_fc2;
     const void *f_qkv, *f_o, *f_fc1, *f_fc2;  // fragment-major 16-bit weights
 };
+constexpr int kSeqMaxLayers = 32;
 struct SeqArgs {
-    const SeqLayer *layers;
+    SeqLayer layers[kSeqMaxLayers];  // in the kernel-argument segment: read with scalar loads, no pointer chasing
     int n_layers, ratio;
     const float *lnf_g, *lnf_b, *b_head;
     const void *f_head;

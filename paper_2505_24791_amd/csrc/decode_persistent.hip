@@ -33,7 +33,7 @@ namespace {
 constexpr int P_NW = 8;  // waves per workgroup
 constexpr int P_THREADS = 64 * P_NW;
 constexpr int P_CB = 4;  // 16-column blocks per round of a LayerNorm-fused projection
-constexpr int P_CBR = 2; // the same for the residual projections
+constexpr int P_EB = 2;  // embedding column blocks of a member whose w_in slice is kept in LDS
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
@@ -57,7 +57,32 @@ struct Ctx {
     int epoch;
     int *cnt, *status;
     int spin_max;
+#ifdef SJD_SEQ_TIMELINE
+    int *tl; int *tl_k; bool tl_on; long long tl_t0;   // tl_k: counter in LDS
+#endif
 };
+
+// Development aid, compiled in only with -DSJD_SEQ_TIMELINE: member 0 of group 0 records the 100 MHz
+// clock at stage boundaries (and a few points inside stages) of one step into the tail of the
+// synchronisation words.
+#ifdef SJD_SEQ_TIMELINE
+#define SJD_TLC(cc_) do { if ((cc_).tl_on && (cc_).tid == 0) { const int k_ = (*(cc_).tl_k)++; if (k_ < 300) (cc_).tl[k_] = (int)(wall_clock64() - (cc_).tl_t0); } } while (0)
+#else
+#define SJD_TLC(c) do { } while (0)
+#endif
+
+// A copy of the per-thread indices that the optimiser cannot see through: addresses derived from it
+// are recomputed where they are used instead of being hoisted out of the step loop and kept in
+// registers for the whole kernel (which costs far more than the few integer instructions).
+__device__ __forceinline__ Ctx local_ctx(const Ctx &c) {
+    Ctx d = c;
+    asm volatile("" : "+v"(d.lane), "+v"(d.tid), "+v"(d.r), "+v"(d.kg));
+    d.wave = __builtin_amdgcn_readfirstlane(d.wave);
+    d.slot = __builtin_amdgcn_readfirstlane(d.slot);
+    d.rb0 = __builtin_amdgcn_readfirstlane(d.rb0);
+    asm volatile("" : "+s"(d.wave), "+s"(d.slot), "+s"(d.rb0));
+    return d;
+}
 
 // Barrier among the workgroups of one group (see the header).  Returns false after a time-out.
 __device__ __forceinline__ bool group_barrier(Ctx &c, volatile int *sh_ok) {
@@ -80,23 +105,49 @@ __device__ __forceinline__ bool group_barrier(Ctx &c, volatile int *sh_ok) {
     return *sh_ok != 0;
 }
 
+// Weight fragments of a stage, fetched ahead of the barrier that precedes the stage (weights do
+// not depend on what the other members are still computing).
+template <typename HT, int S> struct LnPre { typename Half16<HT>::v8 f[P_CB][S]; };
+template <typename HT, int S, int KMUL> struct ResPre { typename Half16<HT>::v8 f[KMUL * S]; };
+struct NoPrefetch { __device__ __forceinline__ void operator()() const {} };
+
+// first-round weights of a LayerNorm-fused projection: column blocks slot, slot+n, ... (clamped, so
+// that the loads are unconditional; blocks past the end are never used)
+template <typename HT, int S>
+__device__ __forceinline__ void ln_prefetch(const Ctx &c, const HT *__restrict__ Wt, int N, int cb0, LnPre<HT, S> &w) {
+    typedef typename Half16<HT>::v8 v8;
+    constexpr int KS = 8 * S;
+    const int nbt = (N + 15) >> 4;
+#pragma unroll
+    for (int cc = 0; cc < P_CB; ++cc) {
+        int cb = cb0 + cc * c.n;
+        cb = cb < nbt ? cb : nbt - 1;
+#pragma unroll
+        for (int s = 0; s < S; ++s)
+            w.f[cc][s] = *reinterpret_cast<const v8 *>(Wt + (((size_t)cb * KS + c.wave * S + s) * 64 + c.lane) * 8);
+    }
+}
+
 // C[:, cols of this member] = epi(LayerNorm(Hs) * Wt^T + bias) for the group's 16*MB workspace rows,
 // K = W = 256 S.  Hs float32 fragment-major (read through L2), Wt fragment-major, C fragment-major
 // when 16-bit, row-major [row, N] when float.  Column block cb belongs to member cb % n.
-template <typename HT, int MB, int S, int EPI, typename OutT>
-__device__ __forceinline__ void ln_gemm_stage(const Ctx &c, rsrc_t hs_rs, const float *__restrict__ g,
+// pre: the weights of the first round; pf(): issues the next stage's weight loads (called once the
+// activation loads of this stage are under way).
+template <typename HT, int MB, int S, int EPI, typename OutT, class PF>
+__device__ __forceinline__ void ln_gemm_stage(const Ctx &c_in, rsrc_t hs_rs, const float *__restrict__ g,
                                               const float *__restrict__ be, const HT *__restrict__ Wt,
                                               const float *__restrict__ bias, OutT *C, int N, f32x4v *red,
-                                              float *stat) {
+                                              float *stat, LnPre<HT, S> &pre, PF pf) {
     typedef typename Half16<HT>::v8 v8;
-    constexpr int KS = 8 * S, W = 256 * S;
+    constexpr int W = 256 * S;
+    const Ctx c = local_ctx(c_in);
     const int k0 = c.wave * 32 * S + c.kg * 8;
     f32x4 xr[MB][S][2];
 #pragma unroll
     for (int i = 0; i < MB; ++i)
 #pragma unroll
         for (int s = 0; s < S; ++s) {
-            const uint32_t off = (uint32_t)((((c.rb0 + i) * KS + c.wave * S + s) * 64 + c.lane) * 8) * 4u;
+            const uint32_t off = (uint32_t)((((c.rb0 + i) * (8 * S) + c.wave * S + s) * 64 + c.lane) * 8) * 4u;
             xr[i][s][0] = __builtin_bit_cast(f32x4, ld16_l2(hs_rs, off));
             xr[i][s][1] = __builtin_bit_cast(f32x4, ld16_l2(hs_rs, off + 16u));
         }
@@ -108,6 +159,17 @@ __device__ __forceinline__ void ln_gemm_stage(const Ctx &c, rsrc_t hs_rs, const 
         br[s][0] = *reinterpret_cast<const f32x4 *>(be + k0 + 32 * s);
         br[s][1] = *reinterpret_cast<const f32x4 *>(be + k0 + 32 * s + 4);
     }
+    // bias of the output blocks this wave will finish in the first round (q = wave, wave + 8, ...)
+    const int nbt = (N + 15) >> 4;
+    constexpr int NQ = (P_CB * MB + P_NW - 1) / P_NW;
+    float bv0[NQ];
+#pragma unroll
+    for (int qi = 0; qi < NQ; ++qi) {
+        const int q = c.wave + qi * P_NW;
+        const int col = (c.slot + (q / MB) * c.n) * 16 + c.r;
+        bv0[qi] = (q < P_CB * MB && col < N) ? bias[col] : 0.f;
+    }
+    pf();
     // row statistics: mean, then centred sum of squares; partial sums of the 8 waves meet in LDS
     float mean[MB], rstd[MB];
 #pragma unroll
@@ -151,6 +213,7 @@ __device__ __forceinline__ void ln_gemm_stage(const Ctx &c, rsrc_t hs_rs, const 
         for (int w = 1; w < P_NW; ++w) t += stat[w * (MB * 16) + i * 16 + c.r];
         rstd[i] = 1.0f / sqrtf(t * (1.0f / (float)W) + 1e-5f);
     }
+    SJD_TLC(c);   // statistics done (activations have arrived)
     v8 fa[MB][S];
 #pragma unroll
     for (int i = 0; i < MB; ++i)
@@ -163,33 +226,25 @@ __device__ __forceinline__ void ln_gemm_stage(const Ctx &c, rsrc_t hs_rs, const 
                     fa[i][s][4 * h2 + e] =
                         from_f32<HT>((xr[i][s][h2][e] - mean[i]) * rstd[i] * gr[s][h2][e] + br[s][h2][e]);
 
-    const int nbt = (N + 15) >> 4;
     for (int cb0 = c.slot; cb0 < nbt; cb0 += P_CB * c.n) {
+        if (cb0 != c.slot) ln_prefetch<HT, S>(c, Wt, N, cb0, pre);  // later rounds: fetched here
         f32x4v acc[P_CB][MB];
 #pragma unroll
         for (int cc = 0; cc < P_CB; ++cc)
 #pragma unroll
-            for (int i = 0; i < MB; ++i) acc[cc][i] = f32x4v{0.f, 0.f, 0.f, 0.f};
+            for (int i = 0; i < MB; ++i) {
+                acc[cc][i] = f32x4v{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int cc = 0; cc < P_CB; ++cc) {
-            const int cb = cb0 + cc * c.n;
-            if (cb < nbt) {
-#pragma unroll
-                for (int s = 0; s < S; ++s) {
-                    const v8 fb =
-                        *reinterpret_cast<const v8 *>(Wt + (((size_t)cb * KS + c.wave * S + s) * 64 + c.lane) * 8);
-#pragma unroll
-                    for (int i = 0; i < MB; ++i) acc[cc][i] = Mfma16<HT>::run(fa[i][s], fb, acc[cc][i]);
-                }
+                for (int s = 0; s < S; ++s) acc[cc][i] = Mfma16<HT>::run(fa[i][s], pre.f[cc][s], acc[cc][i]);
+                red[(c.wave * (P_CB * MB) + cc * MB + i) * 64 + c.lane] = acc[cc][i];
             }
-        }
-#pragma unroll
-        for (int cc = 0; cc < P_CB; ++cc)
-#pragma unroll
-            for (int i = 0; i < MB; ++i) red[(c.wave * (P_CB * MB) + cc * MB + i) * 64 + c.lane] = acc[cc][i];
         __syncthreads();
+        SJD_TLC(c);   // partial sums in LDS
         // output block q = (cc, i) is summed in wave order and finished by wave q % 8
-        for (int q = c.wave; q < P_CB * MB; q += P_NW) {
+#pragma unroll
+        for (int qi = 0; qi < NQ; ++qi) {
+            const int q = c.wave + qi * P_NW;
+            if (q >= P_CB * MB) break;
             const int cc = q / MB, i = q % MB;
             const int cb = cb0 + cc * c.n;
             const int col = cb * 16 + c.r;
@@ -197,7 +252,7 @@ __device__ __forceinline__ void ln_gemm_stage(const Ctx &c, rsrc_t hs_rs, const 
                 f32x4v t = red[q * 64 + c.lane];
 #pragma unroll
                 for (int w = 1; w < P_NW; ++w) t += red[(w * (P_CB * MB) + q) * 64 + c.lane];
-                const float bv = bias[col];
+                const float bv = cb0 == c.slot ? bv0[qi] : bias[col];
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     const int row = (c.rb0 + i) * 16 + 4 * c.kg + v;
@@ -212,163 +267,245 @@ __device__ __forceinline__ void ln_gemm_stage(const Ctx &c, rsrc_t hs_rs, const 
     }
 }
 
-// Hs[:, cols of this member] += A * Wt^T + bias for the group's rows; N = W = 256 S, K = kmul * W.
-// A 16-bit fragment-major (read through L2), Hs float32 fragment-major (read through L2, written).
-template <typename HT, int MB, int S>
-__device__ __forceinline__ void gemm_resid_stage(const Ctx &c, rsrc_t a_rs, int kmul, const HT *__restrict__ Wt,
-                                                 const float *__restrict__ bias, rsrc_t hs_rs, float *hs,
-                                                 f32x4v *red) {
+// weights of one column block of a residual projection: the KMUL*S k-steps of this wave
+template <typename HT, int S, int KMUL>
+__device__ __forceinline__ void res_prefetch(const Ctx &c, const HT *__restrict__ Wt, int cb, ResPre<HT, S, KMUL> &w) {
     typedef typename Half16<HT>::v8 v8;
-    constexpr int W = 256 * S, KSN = W / 32;
-    const int KSA = 8 * S * kmul;  // k-steps of the whole K
-    const int ksw = S * kmul;      // k-steps of one wave
-    constexpr int nbt = W / 16;
-    for (int cb0 = c.slot; cb0 < nbt; cb0 += P_CBR * c.n) {
-        f32x4v acc[P_CBR][MB];
+    constexpr int nbt = 16 * S, KSA = 8 * S * KMUL, KSW = S * KMUL;
+    cb = cb < nbt ? cb : nbt - 1;
 #pragma unroll
-        for (int cc = 0; cc < P_CBR; ++cc)
+    for (int u = 0; u < KSW; ++u)
+        w.f[u] = *reinterpret_cast<const v8 *>(Wt + (((size_t)cb * KSA + c.wave * KSW + u) * 64 + c.lane) * 8);
+}
+
+// Hs[:, cols of this member] += A * Wt^T + bias for the group's rows; N = W = 256 S, K = KMUL * W.
+// A 16-bit fragment-major (read through L2), Hs float32 fragment-major (read through L2, written).
+template <typename HT, int MB, int S, int KMUL, class PF>
+__device__ __forceinline__ void gemm_resid_stage(const Ctx &c_in, rsrc_t a_rs, const HT *__restrict__ Wt,
+                                                 const float *__restrict__ bias, rsrc_t hs_rs, float *hs,
+                                                 f32x4v *red, ResPre<HT, S, KMUL> &pre, PF pf) {
+    typedef typename Half16<HT>::v8 v8;
+    constexpr int W = 256 * S, KSN = W / 32, nbt = W / 16, KSA = 8 * S * KMUL, KSW = S * KMUL;
+    const Ctx c = local_ctx(c_in);
+    v8 fa[MB][KSW];
 #pragma unroll
-            for (int i = 0; i < MB; ++i) acc[cc][i] = f32x4v{0.f, 0.f, 0.f, 0.f};
-        for (int ch = 0; ch < kmul; ++ch) {
-            const int ks0 = c.wave * ksw + ch * S;
-            v8 fa[MB][S];
+    for (int i = 0; i < MB; ++i)
 #pragma unroll
-            for (int i = 0; i < MB; ++i)
-#pragma unroll
-                for (int u = 0; u < S; ++u) {
-                    const uint32_t off = (uint32_t)((((c.rb0 + i) * KSA + ks0 + u) * 64 + c.lane) * 8) * 2u;
-                    fa[i][u] = __builtin_bit_cast(v8, ld16_l2(a_rs, off));
-                }
-#pragma unroll
-            for (int cc = 0; cc < P_CBR; ++cc) {
-                const int cb = cb0 + cc * c.n;
-                if (cb < nbt) {
-#pragma unroll
-                    for (int u = 0; u < S; ++u) {
-                        const v8 fb =
-                            *reinterpret_cast<const v8 *>(Wt + (((size_t)cb * KSA + ks0 + u) * 64 + c.lane) * 8);
-#pragma unroll
-                        for (int i = 0; i < MB; ++i) acc[cc][i] = Mfma16<HT>::run(fa[i][u], fb, acc[cc][i]);
-                    }
-                }
-            }
+        for (int u = 0; u < KSW; ++u) {
+            const uint32_t off = (uint32_t)((((c.rb0 + i) * KSA + c.wave * KSW + u) * 64 + c.lane) * 8) * 2u;
+            fa[i][u] = __builtin_bit_cast(v8, ld16_l2(a_rs, off));
         }
+    // the finishing wave (wave i for row block i) fetches its residual values and bias early
+    float rv[4] = {0.f, 0.f, 0.f, 0.f}, bv = 0.f;
+    size_t eo[4] = {0, 0, 0, 0};
+    auto fetch_resid = [&](int cb) {
+        const int col = cb * 16 + c.r;
+        if (c.wave < MB && cb < nbt) {
 #pragma unroll
-        for (int cc = 0; cc < P_CBR; ++cc)
-#pragma unroll
-            for (int i = 0; i < MB; ++i) red[(c.wave * (P_CBR * MB) + cc * MB + i) * 64 + c.lane] = acc[cc][i];
-        __syncthreads();
-        for (int q = c.wave; q < P_CBR * MB; q += P_NW) {
-            const int cc = q / MB, i = q % MB;
-            const int cb = cb0 + cc * c.n;
-            if (cb < nbt) {
-                const int col = cb * 16 + c.r;
-                float rv[4];
-                size_t eo[4];
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    eo[v] = frag_off((c.rb0 + i) * 16 + 4 * c.kg + v, col, KSN);
-                    rv[v] = ld4_l2(hs_rs, (uint32_t)eo[v] * 4u);
-                }
-                f32x4v t = red[q * 64 + c.lane];
-#pragma unroll
-                for (int w = 1; w < P_NW; ++w) t += red[(w * (P_CBR * MB) + q) * 64 + c.lane];
-                const float bv = bias[col];
-#pragma unroll
-                for (int v = 0; v < 4; ++v) hs[eo[v]] = (t[v] + bv) + rv[v];
+            for (int v = 0; v < 4; ++v) {
+                eo[v] = frag_off((c.rb0 + c.wave) * 16 + 4 * c.kg + v, col, KSN);
+                rv[v] = ld4_l2(hs_rs, (uint32_t)eo[v] * 4u);
             }
+            bv = bias[col];
+        }
+    };
+    fetch_resid(c.slot);
+    pf();
+    for (int cb = c.slot; cb < nbt; cb += c.n) {
+        if (cb != c.slot) { res_prefetch<HT, S, KMUL>(c, Wt, cb, pre); fetch_resid(cb); }
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
+            f32x4v acc = f32x4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int u = 0; u < KSW; ++u) acc = Mfma16<HT>::run(fa[i][u], pre.f[u], acc);
+            red[(c.wave * MB + i) * 64 + c.lane] = acc;
+        }
+        SJD_TLC(c);   // operands have arrived, products done
+        __syncthreads();
+        SJD_TLC(c);
+        if (c.wave < MB) {
+            f32x4v t = red[c.wave * 64 + c.lane];
+#pragma unroll
+            for (int w = 1; w < P_NW; ++w) t += red[(w * MB + c.wave) * 64 + c.lane];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) hs[eo[v]] = (t[v] + bv) + rv[v];
         }
         __syncthreads();
     }
 }
 
 // Single-token attention of the group's (sample, head) pairs against the cache at position t:
-// pair (row, h) belongs to member (row * H + h) % n.  The workgroup's 512 threads are 64 key
-// groups x 8 sixteen-byte chunks of the head.  This step's k and v are appended to the cache.
+// pair (row, h) belongs to member (row * H + h) % n.  A pair is handled by four waves (32 key
+// groups x 8 sixteen-byte chunks of the head), two pairs at a time per workgroup; the partition
+// of the keys and the order of the partial sums are the same for every batch size.  This step's k
+// and v are appended to the cache.  Cached rows do not depend on the current step, so the first
+// P_AU rows of every thread (keys and values) are requested before the barrier that precedes
+// the stage (att_prefetch) and only q and the fresh row are waited for afterwards.
+constexpr int P_NSUB = 2;
+constexpr int P_AU = 8;  // cache rows per thread and batch
+template <typename HT> struct AttPre { typename Half16<HT>::v8 k[P_AU], v[P_AU]; };
+
 template <typename HT, int S>
-__device__ __forceinline__ void attention_stage(const Ctx &c, rsrc_t qkv_rs, HT *kc, HT *vc, rsrc_t kc_rs, rsrc_t vc_rs,
-                                                HT *o, int t, int T, float *sc, float *opart, float *wred) {
+__device__ __forceinline__ void att_fetch(const Ctx &c, rsrc_t kc_rs, rsrc_t vc_rs, int k0, int j0, int t, int T,
+                                          AttPre<HT> &w) {
+    typedef typename Half16<HT>::v8 v8;
+    constexpr int W = 256 * S, H = W / 64;
+    const int sub = c.tid >> 8, stid = c.tid & 255, dc = stid & 7, sg = stid >> 3;
+    const int npairs = c.nrows * H;
+    int pi = c.slot + (k0 + sub) * c.n;
+    pi = pi < npairs ? pi : 0;
+    const int row = pi / H, h = pi - row * H;
+    const size_t cbase = ((size_t)(c.row0 + row) * T) * W + h * 64;
+#pragma unroll
+    for (int u = 0; u < P_AU; ++u) {
+        const int s = sg + 32 * (j0 + u);
+        const int sr = s < t ? s : 0;                      // rows at or past t: any cached row, value not used
+        const uint32_t off = (uint32_t)(cbase + (size_t)sr * W + dc * 8) * 2u;
+        w.k[u] = __builtin_bit_cast(v8, ld16_l2(kc_rs, off));
+        w.v[u] = __builtin_bit_cast(v8, ld16_l2(vc_rs, off));
+    }
+}
+
+template <typename HT, int S>
+__device__ __forceinline__ void attention_stage(const Ctx &c_in, rsrc_t qkv_rs, HT *kc, HT *vc, rsrc_t kc_rs, rsrc_t vc_rs,
+                                                HT *o, int t, int T, float *sc_all, float *opart, float *wred) {
     typedef typename Half16<HT>::v8 v8;
     constexpr int W = 256 * S, H = W / 64, KS3 = 3 * W / 32;
-    const int dc = c.tid & 7, sg = c.tid >> 3;
+    const Ctx c = local_ctx(c_in);
+    const int sub = c.tid >> 8, stid = c.tid & 255;
+    const int dc = stid & 7, sg = stid >> 3;               // chunk of the head, key group (0..31)
+    float *sc = sc_all + (size_t)sub * T;
     const int npairs = c.nrows * H;
-    for (int pi = c.slot; pi < npairs; pi += c.n) {
-        const int row = pi / H, h = pi - row * H;
+    const int mine = npairs > c.slot ? (npairs - c.slot + c.n - 1) / c.n : 0;   // pairs of this member
+    const int nk = t + 1;
+    const int nbatch = (nk + 32 * P_AU - 1) / (32 * P_AU);  // batches of P_AU rows per thread
+    for (int k0 = 0; k0 < mine; k0 += P_NSUB) {
+        const int pi = c.slot + (k0 + sub) * c.n;
+        const bool valid = (k0 + sub) < mine;
+        const int row = valid ? pi / H : 0, h = valid ? pi - row * H : 0;
         const int b = c.row0 + row, wsrow = c.rb0 * 16 + row;
         auto chunk = [&](int part, int ci) -> v8 {
             return __builtin_bit_cast(v8, ld16_l2(qkv_rs, (uint32_t)frag_off(wsrow, part * W + h * 64 + ci * 8, KS3) * 2u));
         };
-        const v8 kfresh = chunk(1, dc), vfresh = chunk(2, dc);
+        const v8 kfresh = chunk(1, dc), vfresh = chunk(2, dc), q8 = chunk(0, dc);
         const size_t cbase = ((size_t)b * T) * W + h * 64;
-        if (c.tid < 8) *reinterpret_cast<v8 *>(kc + cbase + (size_t)t * W + c.tid * 8) = chunk(1, c.tid);
-        else if (c.tid < 16) *reinterpret_cast<v8 *>(vc + cbase + (size_t)t * W + (c.tid - 8) * 8) = chunk(2, c.tid - 8);
-        float qf[8];
-        {
-            const v8 q8 = chunk(0, dc);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) qf[e] = (float)q8[e] * 0.125f;  // 1/sqrt(64)
+        if (valid) {
+            if (stid < 8) *reinterpret_cast<v8 *>(kc + cbase + (size_t)t * W + stid * 8) = chunk(1, stid);
+            else if (stid < 16) *reinterpret_cast<v8 *>(vc + cbase + (size_t)t * W + (stid - 8) * 8) = chunk(2, stid - 8);
         }
-        const int nk = t + 1;
+        float qf[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qf[e] = (float)q8[e] * 0.125f;  // 1/sqrt(64)
+        AttPre<HT> pre;
+        att_fetch<HT, S>(c, kc_rs, vc_rs, k0, 0, t, T, pre);   // first batch of cached keys and values, in one go
+        // scores of batch 0 (values stay in registers), further batches fetch keys only
         float mx = -INFINITY;
-        for (int s = sg; s < nk; s += 64) {
-            const v8 k8 = s < t ? __builtin_bit_cast(v8, ld16_l2(kc_rs, (uint32_t)(cbase + (size_t)s * W + dc * 8) * 2u))
-                                : kfresh;
+        float d0[P_AU];
+#pragma unroll
+        for (int u = 0; u < P_AU; ++u) {
+            const int s = sg + 32 * u;
+            const v8 k8 = s < t ? pre.k[u] : kfresh;
             float d = 0.f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) d = fmaf(qf[e], (float)k8[e], d);
             d += __shfl_xor(d, 1, 64);
             d += __shfl_xor(d, 2, 64);
             d += __shfl_xor(d, 4, 64);
-            if (dc == 0) sc[s] = d;
-            mx = fmaxf(mx, d);
+            d0[u] = d;
+            if (s < nk) mx = fmaxf(mx, d);
+        }
+        for (int jb = 1; jb < nbatch; ++jb) {
+            v8 kk[P_AU];
+#pragma unroll
+            for (int u = 0; u < P_AU; ++u) {
+                const int s = sg + 32 * (jb * P_AU + u);
+                const int sr = s < t ? s : 0;
+                kk[u] = __builtin_bit_cast(v8, ld16_l2(kc_rs, (uint32_t)(cbase + (size_t)sr * W + dc * 8) * 2u));
+            }
+#pragma unroll
+            for (int u = 0; u < P_AU; ++u) {
+                const int s = sg + 32 * (jb * P_AU + u);
+                const v8 k8 = s < t ? kk[u] : kfresh;
+                float d = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) d = fmaf(qf[e], (float)k8[e], d);
+                d += __shfl_xor(d, 1, 64);
+                d += __shfl_xor(d, 2, 64);
+                d += __shfl_xor(d, 4, 64);
+                if (s < nk) {
+                    if (dc == 0) sc[s] = d;
+                    mx = fmaxf(mx, d);
+                }
+            }
         }
         mx = wave_max(mx);
+        SJD_TLC(c);   // scores done (q, fresh row and cached keys have arrived)
         if (c.lane == 0) wred[c.wave] = mx;
         __syncthreads();
-        mx = wred[0];
-#pragma unroll
-        for (int w = 1; w < P_NW; ++w) mx = fmaxf(mx, wred[w]);
+        SJD_TLC(c);
+        mx = fmaxf(fmaxf(wred[4 * sub], wred[4 * sub + 1]), fmaxf(wred[4 * sub + 2], wred[4 * sub + 3]));
         float acc[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[e] = 0.f;
         float psum = 0.f;
-        for (int s = sg; s < nk; s += 64) {
-            const float p = expf(sc[s] - mx);
-            const v8 v8v = s < t ? __builtin_bit_cast(v8, ld16_l2(vc_rs, (uint32_t)(cbase + (size_t)s * W + dc * 8) * 2u))
-                                 : vfresh;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[e] = fmaf(p, (float)v8v[e], acc[e]);
-            psum += p;
+        for (int u = 0; u < P_AU; ++u) {
+            const int s = sg + 32 * u;
+            if (s < nk) {
+                const float p = expf(d0[u] - mx);
+                const v8 v8v = s < t ? pre.v[u] : vfresh;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[e] = fmaf(p, (float)v8v[e], acc[e]);
+                psum += p;
+            }
         }
-        // the 8 key groups of a wave (lanes differing in bits 3..5), then the 8 waves in index order
+        for (int jb = 1; jb < nbatch; ++jb) {
+            v8 vv[P_AU];
+#pragma unroll
+            for (int u = 0; u < P_AU; ++u) {
+                const int s = sg + 32 * (jb * P_AU + u);
+                const int sr = s < t ? s : 0;
+                vv[u] = __builtin_bit_cast(v8, ld16_l2(vc_rs, (uint32_t)(cbase + (size_t)sr * W + dc * 8) * 2u));
+            }
+#pragma unroll
+            for (int u = 0; u < P_AU; ++u) {
+                const int s = sg + 32 * (jb * P_AU + u);
+                if (s < nk) {
+                    const float p = expf(sc[s] - mx);
+                    const v8 v8v = s < t ? vv[u] : vfresh;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc[e] = fmaf(p, (float)v8v[e], acc[e]);
+                    psum += p;
+                }
+            }
+        }
+        // the 8 key groups of a wave (lanes differing in bits 3..5), then the pair's four waves in order
 #pragma unroll
         for (int off = 8; off < 64; off <<= 1) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc[e] += __shfl_xor(acc[e], off, 64);
             psum += __shfl_xor(psum, off, 64);
         }
+        SJD_TLC(c);   // weighted values summed within the wave
         if (c.lane < 8) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) opart[c.wave * 64 + c.lane * 8 + e] = acc[e];
             if (c.lane == 0) wred[P_NW + c.wave] = psum;
         }
         __syncthreads();
-        if (c.tid < 8) {
-            float den = wred[P_NW];
-#pragma unroll
-            for (int w = 1; w < P_NW; ++w) den += wred[P_NW + w];
+        if (valid && stid < 8) {
+            const int w0 = 4 * sub;
+            const float den = ((wred[P_NW + w0] + wred[P_NW + w0 + 1]) + wred[P_NW + w0 + 2]) + wred[P_NW + w0 + 3];
             v8 ov;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const int d = c.tid * 8 + e;
-                float sum = opart[d];
-#pragma unroll
-                for (int w = 1; w < P_NW; ++w) sum += opart[w * 64 + d];
-                ov[e] = from_f32<HT>(sum / den);
+                const int d = stid * 8 + e;
+                ov[e] = from_f32<HT>((((opart[w0 * 64 + d] + opart[(w0 + 1) * 64 + d]) + opart[(w0 + 2) * 64 + d]) +
+                                      opart[(w0 + 3) * 64 + d]) / den);
             }
-            *reinterpret_cast<v8 *>(o + frag_off(wsrow, h * 64 + c.tid * 8, W / 32)) = ov;
+            *reinterpret_cast<v8 *>(o + frag_off(wsrow, h * 64 + stid * 8, W / 32)) = ov;
         }
-        __syncthreads();  // sc, opart and wred are reused by the next pair
+        __syncthreads();  // sc, opart and wred are reused by the next round
     }
 }
 
@@ -382,7 +519,8 @@ __global__ __launch_bounds__(P_THREADS) void seq_persistent_kernel(SeqArgs a) {
     float *xs = stat + P_NW * MB * 16;                                        // [16*MB][D]
     float *opart = xs + RW_ROWS * a.D;                                        // [8][64]
     float *wred = opart + P_NW * 64;                                          // [16]
-    float *sc = wred + 16;                                                    // [T]
+    float *sc = wred + 16;                                                    // [2][T]
+    float *wemb = sc + 2 * a.T;                                               // [P_EB][D + 1][16]: w_in slice, then b_in
 
     Ctx c;
     c.tid = threadIdx.x; c.lane = c.tid & 63; c.wave = c.tid >> 6; c.r = c.lane & 15; c.kg = c.lane >> 4;
@@ -431,36 +569,86 @@ __global__ __launch_bounds__(P_THREADS) void seq_persistent_kernel(SeqArgs a) {
     const rsrc_t ff_rs = make_rsrc(ff, ws_rows * (uint32_t)a.ratio * W * 2u);
     const rsrc_t p_rs = make_rsrc(a.p, ws_rows * 2u * D * 4u);
     volatile int *sh_ok = &sh[6];
+    // this member's slices of the embedding matrix and bias stay in LDS for the whole block
+    for (int bi = 0, cb = c.slot; bi < P_EB && cb < W / 16; ++bi, cb += c.n)
+        for (int e = c.tid; e < (D + 1) * 16; e += P_THREADS) {
+            const int d = e >> 4, cl = e & 15;
+            wemb[(size_t)bi * (D + 1) * 16 + e] = d < D ? a.w_in[(size_t)d * W + cb * 16 + cl] : a.b_in[cb * 16 + cl];
+        }
+    // latent values of position 0 (each thread keeps the ones it will turn into x)
+    constexpr int ZPT = (RW_ROWS * 64 + P_THREADS - 1) / P_THREADS;   // token sizes up to 64
+    float zreg[ZPT];
+#pragma unroll
+    for (int q = 0; q < ZPT; ++q) {
+        const int e = c.tid + q * P_THREADS;
+        zreg[q] = 0.f;
+        if (e < RW_ROWS * D) {
+            const int row = e / D, d = e - row * D;
+            if (row < c.nrows) zreg[q] = a.z[((size_t)(c.row0 + row) * T + (a.reversed ? T - 1 : 0)) * D + d];
+        }
+    }
+    __syncthreads();
 
     for (int l = 0; l < T; ++l) {
-        // ---- x_l of the group's samples (eq. 5; x_0 = z_0), kept in LDS for the embedding
+#ifdef SJD_SEQ_TIMELINE
+        Ctx &cm = const_cast<Ctx &>(c);
+        cm.tl_on = gidx == 0 && c.slot == 0 && l == T / 2;
+        cm.tl = a.sync + 640; cm.tl_t0 = wall_clock64(); cm.tl_k = &sh[7]; if (c.tid == 0) sh[7] = 0;
+#endif
+        // ---- x_l of the group's samples (eq. 5; x_0 = z_0), kept in LDS for the embedding; the latent
+        // values were requested one step ahead
         const int tok = a.reversed ? T - 1 - l : l;
-        for (int e = c.tid; e < RW_ROWS * D; e += P_THREADS) {
-            const int row = e / D, d = e - row * D;
-            float xn = 0.f;
-            if (row < c.nrows) {
-                const size_t idx = ((size_t)(c.row0 + row) * T + tok) * D + d;
-                xn = a.z[idx];
-                if (l > 0) {
-                    const uint32_t po = (uint32_t)((c.rb0 * 16 + row) * 2 * D + d) * 4u;
-                    xn = fmaf(xn, expf(ld4_l2(p_rs, po + (uint32_t)D * 4u)), ld4_l2(p_rs, po));
+        const int tok_next = a.reversed ? T - 2 - l : l + 1;
+#pragma unroll
+        for (int q = 0; q < ZPT; ++q) {
+            const int e = c.tid + q * P_THREADS;
+            if (e < RW_ROWS * D) {
+                const int row = e / D, d = e - row * D;
+                float xn = 0.f;
+                if (row < c.nrows) {
+                    const size_t idx = ((size_t)(c.row0 + row) * T + tok) * D + d;
+                    xn = zreg[q];
+                    if (l > 0) {
+                        const uint32_t po = (uint32_t)((c.rb0 * 16 + row) * 2 * D + d) * 4u;
+                        xn = fmaf(xn, expf(ld4_l2(p_rs, po + (uint32_t)D * 4u)), ld4_l2(p_rs, po));
+                    }
+                    if (c.slot == 0) a.x[idx] = xn;
+                    if (l + 1 < T) zreg[q] = a.z[((size_t)(c.row0 + row) * T + tok_next) * D + d];
                 }
-                if (c.slot == 0) a.x[idx] = xn;
+                xs[e] = xn;
             }
-            xs[e] = xn;
         }
         if (l == T - 1) break;
         __syncthreads();
         // ---- embedding of this member's column blocks: hs = x_l * w_in + b_in + pos[l]
-        for (int cb = c.slot; cb < W / 16; cb += c.n) {
-            for (int e = c.tid; e < RW_ROWS * 16; e += P_THREADS) {
-                const int row = e >> 4, col = cb * 16 + (e & 15);
-                float acc = a.b_in[col] + a.pos[(size_t)l * W + col];
-                for (int d = 0; d < D; ++d) acc = fmaf(xs[row * D + d], a.w_in[(size_t)d * W + col], acc);
-                a.hs[frag_off(c.rb0 * 16 + row, col, W / 32)] = acc;
+        {
+            int bi = 0;
+            for (int cb = c.slot; cb < W / 16; cb += c.n, ++bi) {
+                for (int e = c.tid; e < RW_ROWS * 16; e += P_THREADS) {
+                    const int row = e >> 4, cl = e & 15, col = cb * 16 + cl;
+                    float acc = a.pos[(size_t)l * W + col];
+                    if (bi < P_EB) {
+                        const float *we = wemb + (size_t)bi * (D + 1) * 16;
+                        acc += we[D * 16 + cl];
+                        for (int d = 0; d < D; ++d) acc = fmaf(xs[row * D + d], we[d * 16 + cl], acc);
+                    } else {
+                        acc += a.b_in[col];
+                        for (int d = 0; d < D; ++d) acc = fmaf(xs[row * D + d], a.w_in[(size_t)d * W + col], acc);
+                    }
+                    a.hs[frag_off(c.rb0 * 16 + row, col, W / 32)] = acc;
+                }
             }
         }
+        // Weights of a stage are requested one stage ahead where the registers allow it (W <= 512),
+        // else at the start of the stage itself.
+        constexpr bool AHEAD = S <= 2;
+        LnPre<HT, S> wln;
+        ResPre<HT, S, 1> wo;
+        ResPre<HT, S, 4> wf2;
+        if (AHEAD) ln_prefetch<HT, S>(c, (const HT *)a.layers[0].f_qkv, 3 * W, c.slot, wln);
+        SJD_TLC(c);
         if (!group_barrier(c, sh_ok)) return;
+        SJD_TLC(c);
 
         for (int ly = 0; ly < a.n_layers; ++ly) {
             const SeqLayer &lw = a.layers[ly];
@@ -468,22 +656,49 @@ __global__ __launch_bounds__(P_THREADS) void seq_persistent_kernel(SeqArgs a) {
             HT *vc = reinterpret_cast<HT *>(a.vcache) + (size_t)ly * a.kv_layer_stride;
             const rsrc_t kc_rs = make_rsrc(kc, (uint32_t)(a.kv_layer_stride * 2u));
             const rsrc_t vc_rs = make_rsrc(vc, (uint32_t)(a.kv_layer_stride * 2u));
+            if (!AHEAD) ln_prefetch<HT, S>(c, (const HT *)lw.f_qkv, 3 * W, c.slot, wln);
             ln_gemm_stage<HT, MB, S, EPI_BIAS, HT>(c, hs_rs, lw.ln1_g, lw.ln1_b, (const HT *)lw.f_qkv, lw.b_qkv, qkv,
-                                                  3 * W, red, stat);
+                                                  3 * W, red, stat, wln, NoPrefetch());
+            SJD_TLC(c);
             if (!group_barrier(c, sh_ok)) return;
+            SJD_TLC(c);
+            if (AHEAD) res_prefetch<HT, S, 1>(c, (const HT *)lw.f_o, c.slot, wo);
             attention_stage<HT, S>(c, qkv_rs, kc, vc, kc_rs, vc_rs, o, l, T, sc, opart, wred);
+            SJD_TLC(c);
             if (!group_barrier(c, sh_ok)) return;
-            gemm_resid_stage<HT, MB, S>(c, o_rs, 1, (const HT *)lw.f_o, lw.b_o, hs_rs, a.hs, red);
+            SJD_TLC(c);
+            if (!AHEAD) res_prefetch<HT, S, 1>(c, (const HT *)lw.f_o, c.slot, wo);
+            gemm_resid_stage<HT, MB, S, 1>(c, o_rs, (const HT *)lw.f_o, lw.b_o, hs_rs, a.hs, red, wo, [&]() {
+                if (AHEAD) ln_prefetch<HT, S>(c, (const HT *)lw.f_fc1, 4 * W, c.slot, wln);
+            });
+            SJD_TLC(c);
             if (!group_barrier(c, sh_ok)) return;
+            SJD_TLC(c);
+            if (!AHEAD) ln_prefetch<HT, S>(c, (const HT *)lw.f_fc1, 4 * W, c.slot, wln);
             ln_gemm_stage<HT, MB, S, EPI_BIAS_GELU, HT>(c, hs_rs, lw.ln2_g, lw.ln2_b, (const HT *)lw.f_fc1, lw.b_fc1, ff,
-                                                       a.ratio * W, red, stat);
+                                                       4 * W, red, stat, wln, [&]() {
+                if (AHEAD) res_prefetch<HT, S, 4>(c, (const HT *)lw.f_fc2, c.slot, wf2);
+            });
+            SJD_TLC(c);
             if (!group_barrier(c, sh_ok)) return;
-            gemm_resid_stage<HT, MB, S>(c, ff_rs, a.ratio, (const HT *)lw.f_fc2, lw.b_fc2, hs_rs, a.hs, red);
+            SJD_TLC(c);
+            const bool last = ly + 1 == a.n_layers;
+            const HT *next_w = (const HT *)(last ? a.f_head : a.layers[last ? ly : ly + 1].f_qkv);
+            const int next_n = last ? 2 * D : 3 * W;
+            if (!AHEAD) res_prefetch<HT, S, 4>(c, (const HT *)lw.f_fc2, c.slot, wf2);
+            gemm_resid_stage<HT, MB, S, 4>(c, ff_rs, (const HT *)lw.f_fc2, lw.b_fc2, hs_rs, a.hs, red, wf2, [&]() {
+                if (AHEAD) ln_prefetch<HT, S>(c, next_w, next_n, c.slot, wln);
+            });
+            SJD_TLC(c);
             if (!group_barrier(c, sh_ok)) return;
+            SJD_TLC(c);
         }
+        if (!AHEAD) ln_prefetch<HT, S>(c, (const HT *)a.f_head, 2 * D, c.slot, wln);
         ln_gemm_stage<HT, MB, S, EPI_BIAS, float>(c, hs_rs, a.lnf_g, a.lnf_b, (const HT *)a.f_head, a.b_head, a.p, 2 * D,
-                                                 red, stat);
+                                                 red, stat, wln, NoPrefetch());
+        SJD_TLC(c);
         if (!group_barrier(c, sh_ok)) return;
+        SJD_TLC(c);
     }
 }
 
@@ -491,7 +706,7 @@ __global__ __launch_bounds__(P_THREADS) void seq_persistent_kernel(SeqArgs a) {
 
 size_t seq_persistent_lds_bytes(int MB, int T, int D) {
     size_t need = (size_t)P_NW * P_CB * MB * 64 * 16 + (size_t)P_NW * MB * 16 * 4 + (size_t)16 * MB * D * 4 +
-                  (size_t)P_NW * 64 * 4 + 16 * 4 + (size_t)T * 4;
+                  (size_t)P_NW * 64 * 4 + 16 * 4 + (size_t)2 * T * 4 + (size_t)P_EB * (D + 1) * 16 * 4;
     const size_t one_per_cu = 84 * 1024;  // more than half of a CU's LDS: exactly one workgroup per CU
     if (need < one_per_cu) need = one_per_cu;
     return (need + 255) & ~(size_t)255;

@@ -46,7 +46,6 @@ struct BlockW {
     const float *w_in, *b_in, *pos, *lnf_g, *lnf_b, *w_head, *b_head;
     void *t_head, *f_head;
     std::vector<LayerW> layer;
-    SeqLayer *seq_layers = nullptr;   // device copy of the per-layer pointers for the persistent sequential kernel
 };
 
 struct ProfSpan { hipEvent_t a, b; int fam; };
@@ -80,7 +79,6 @@ struct sjd_flow {
     int use_graphs = 1;
     int seq_path = 0;            // 0 automatic, 1 per-step launches (graph replay), 2 persistent kernel
     int *psync = nullptr;        // synchronisation words of the persistent kernel (1024 ints)
-    SeqLayer *seq_layers = nullptr;  // [n_blocks][n_layers] on the device
     int n_cus = 0, coop = 0;
     hipEvent_t ev[SJD_MAX_BLOCKS + 1] = {};
     // profiling
@@ -454,11 +452,11 @@ int run_sequential_fast(sjd_flow *f, int j, const float *z, float *x, int batch,
     return SJD_OK;
 }
 
-// The persistent kernel covers: 16-bit modes, head size 64, W in {256, 512, 768, 1024}, batch <= 256,
+// The persistent kernel covers: 16-bit modes, head size 64, W in {256, 512, 768, 1024}, MLP ratio 4, batch <= 256,
 // a cooperative launch of one workgroup per CU, and per-layer caches below 4 GiB (32-bit offsets).
 bool persistent_ok(const sjd_flow *f, int batch) {
     const sjd_config &c = f->cfg;
-    return frag_ok(f, batch) && f->coop && f->n_cus >= 8 && batch <= 256 && c.token_dim <= 256 &&
+    return frag_ok(f, batch) && f->coop && f->n_cus >= 8 && batch <= 256 && c.token_dim <= 64 && c.mlp_ratio == 4 && c.n_layers <= kSeqMaxLayers &&
            (size_t)c.max_batch * c.seq_len * c.width * 2 < ((size_t)1 << 32) &&
            seq_persistent_lds_bytes(batch <= 128 ? 1 : 2, c.seq_len, c.token_dim) <= 160 * 1024;
 }
@@ -468,7 +466,12 @@ int run_sequential_persistent(sjd_flow *f, int j, const float *z, float *x, int 
     const BlockW &bw = f->block[j];
     const int MB = batch <= 128 ? 1 : 2;
     SeqArgs a{};
-    a.layers = bw.seq_layers; a.n_layers = c.n_layers; a.ratio = c.mlp_ratio;
+    a.n_layers = c.n_layers; a.ratio = c.mlp_ratio;
+    for (int l = 0; l < c.n_layers; ++l) {
+        const LayerW &lw = bw.layer[l];
+        a.layers[l] = SeqLayer{lw.ln1_g, lw.ln1_b, lw.b_qkv, lw.b_o, lw.ln2_g, lw.ln2_b, lw.b_fc1, lw.b_fc2,
+                               lw.f_qkv, lw.f_o, lw.f_fc1, lw.f_fc2};
+    }
     a.lnf_g = bw.lnf_g; a.lnf_b = bw.lnf_b; a.b_head = bw.b_head; a.f_head = bw.f_head;
     a.w_in = bw.w_in; a.b_in = bw.b_in; a.pos = bw.pos;
     a.z = z; a.x = x;
@@ -572,7 +575,6 @@ int sjd_flow_create(const sjd_config *cfg, sjd_flow **out) {
     A((void **)&f->active[1], B * 4);
     A((void **)&f->trace, 2 * T * B * 4);
     A((void **)&f->psync, 1024 * sizeof(int));
-    A((void **)&f->seq_layers, (size_t)c.n_blocks * N * sizeof(SeqLayer));
     {
         hipDeviceProp_t prop;
         if (rc == SJD_OK && hipGetDeviceProperties(&prop, f->device) == hipSuccess) {
@@ -676,14 +678,6 @@ int sjd_flow_load_weights(sjd_flow *f, const void *host_blob, size_t nbytes) {
         bw.b_head = p;
         bw.t_head = prep(bw.w_head, W, 2 * D);
         bw.f_head = prep_frag(bw.w_head, W, 2 * D);
-        std::vector<SeqLayer> sl(c.n_layers);
-        for (int l = 0; l < c.n_layers; ++l) {
-            const LayerW &lw = bw.layer[l];
-            sl[l] = SeqLayer{lw.ln1_g, lw.ln1_b, lw.b_qkv, lw.b_o, lw.ln2_g, lw.ln2_b, lw.b_fc1, lw.b_fc2,
-                             lw.f_qkv, lw.f_o, lw.f_fc1, lw.f_fc2};
-        }
-        bw.seq_layers = f->seq_layers + (size_t)j * c.n_layers;
-        HIP_TRY(hipMemcpy(bw.seq_layers, sl.data(), sl.size() * sizeof(SeqLayer), hipMemcpyHostToDevice));
     }
     HIP_TRY(hipDeviceSynchronize());
     HIP_TRY(hipGetLastError());
@@ -866,6 +860,12 @@ int sjd_op_linear_h16(int dtype, int kernel, const void *a_dev, const void *wt_d
     HIP_TRY(hipGetLastError());
     return SJD_OK;
 }
+
+#ifdef SJD_SEQ_TIMELINE
+extern "C" __attribute__((visibility("default"))) int sjd_debug_read_sync(sjd_flow *f, int *out1024) {
+    return hipMemcpy(out1024, f->psync, 1024 * sizeof(int), hipMemcpyDeviceToHost) == hipSuccess ? 0 : -1;
+}
+#endif
 
 int sjd_flow_set_sequential_path(sjd_flow *f, int path) {
     if (!f) return fail(SJD_EINVAL, "null flow");
