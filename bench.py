@@ -25,7 +25,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # Bytes per launch that the L2s requested from / wrote to the memory side, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs of `bench.py --counters`, scaled by what the same counters read for a 256 MiB copy
 # (profiles/bench_c2_hbm_counters.md).  Keyed by (workload, kernel family); anything else reports null.
-MEASURED_TRAFFIC_BYTES = {("C2", "decode_gemm"): 2.97e6}
+MEASURED_TRAFFIC_BYTES = {("C2", "decode_fused"): 7.11e10, ("C2", "decode_gemm"): 2.97e6}
 
 
 def parse():
@@ -45,13 +45,17 @@ def parse():
     ap.add_argument("--mode", default="selective", choices=("selective", "sequential", "jacobi"),
                     help="selective: block 0 sequential, the rest Jacobi (the metric); sequential: every block "
                          "sequential; jacobi: every block Jacobi (uniform Jacobi decoding)")
+    ap.add_argument("--seq-path", type=int, default=0, choices=(0, 1, 2, 3),
+                    help="schedule of sequential blocks: 0 automatic, 1 per-step launches replayed as a graph, 2 "
+                         "persistent kernel (cooperative launch), 3 persistent kernel with an ordinary launch (for "
+                         "runs under rocprofv3, which does not survive cooperative launches here)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-seq", action="store_true", help="skip the GPU all-sequential baseline")
     ap.add_argument("--cpu-samples", type=int, default=0, help="samples for the CPU baseline (0 = one per thread)")
     ap.add_argument("--counters", action="store_true",
                     help="for runs under rocprofv3 --pmc: a plain 256 MiB device copy five times (the known-size "
-                         "kernel that hardware traffic counters are scaled by), then ONE pass of the hot path "
-                         "block by block with plain launches (no graph replay), progress on stderr, no timing")
+                         "kernel that hardware traffic counters are scaled by), then block 0 sequentially and ONE "
+                         "whole-sequence Jacobi pass of block 1, progress on stderr, no timing")
     return ap.parse_args()
 
 
@@ -89,6 +93,7 @@ def main() -> int:
     z_host = wl.make_latent(cfg)
     flow = sjd.Flow(cfg)
     flow.load_weights(blob)
+    flow.set_sequential_path(args.seq_path)
     z = torch.from_numpy(z_host).cuda()
     x = torch.empty_like(z)
     opts = sjd.JacobiOpts(tau=tau, criterion=args.criterion, init=args.init,
@@ -105,12 +110,13 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
         say("copy kernel done: 5 x 256 MiB read + 256 MiB written")
-        flow.profile_enable(range(sjd.PROF_FAMILIES))      # plain launches instead of graph replay
         cur = flow.sequential_inverse_block(0, z)
         say("block 0 (sequential) done")
-        for j in range(1, K):
-            cur, _, passes, _ = flow.jacobi_inverse_block(j, cur, opts)
-            say(f"block {j} (Jacobi) done: {passes} passes")
+        # one whole-sequence pass at the full batch is enough for the per-launch traffic of its kernels
+        # (and keeps the number of dispatches small: the profiler's counter mode does not survive thousands)
+        one = sjd.JacobiOpts(tau=tau, max_iters=1)
+        flow.jacobi_inverse_block(1 if K > 1 else 0, cur, one)
+        say("one Jacobi pass of the next block done")
         flow.close()
         return 0
 

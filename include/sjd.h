@@ -196,7 +196,10 @@ SJD_API int sjd_op_linear_h16(int dtype, int kernel, const void *a_dev, const vo
 /* How sjd_sequential_inverse_block (and the sequential blocks of sjd_sample) run in the 16-bit modes:
  * 0 automatic (the persistent kernel where it applies, else per-step launches), 1 per-step launches
  * replayed as a graph, 2 the persistent kernel (SJD_EINVAL at the call if the configuration is outside
- * what it covers: head size 64, W in {256, 512, 768, 1024}, MLP ratio 4, batch <= 256).  Both compute eq. 5 with the
+ * what it covers: head size 64, W in {256, 512, 768, 1024}, MLP ratio 4, batch <= 256), 3 the persistent
+ * kernel started with an ordinary launch instead of a cooperative one (for tools that cannot follow
+ * cooperative launches; needs an otherwise idle device, and reports SJD_EHIP instead of waiting
+ * forever if its workgroups do not all become resident).  All compute eq. 5 with the
  * key/value cache of Sec. 3.5; they differ in how the T-1 dependent steps are scheduled on the GPU. */
 SJD_API int sjd_flow_set_sequential_path(sjd_flow *flow, int path);
 

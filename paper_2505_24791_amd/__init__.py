@@ -272,7 +272,7 @@ class Flow:
         return x, st, iters
 
     def set_sequential_path(self, path: int) -> None:
-        """0 automatic, 1 per-step launches (graph replay), 2 persistent kernel."""
+        """0 automatic, 1 per-step launches (graph replay), 2 persistent kernel, 3 the same with a plain launch."""
         _check(self.lib.sjd_flow_set_sequential_path(self._h, path))
 
     def profile_enable(self, families) -> None:

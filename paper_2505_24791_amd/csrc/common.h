@@ -227,8 +227,9 @@ struct SeqArgs {
     int spin_max;
 };
 size_t seq_persistent_lds_bytes(int MB, int T, int D);
-// Cooperative launch of one workgroup of 512 threads per CU (grid = number of CUs).  W = 256 S.
-hipError_t launch_seq_persistent(bool is_bf16, const SeqArgs &args, int MB, int S, int grid, hipStream_t s);
+// One workgroup of 512 threads per CU (grid = number of CUs), as a cooperative launch or a plain one.  W = 256 S.
+hipError_t launch_seq_persistent(bool is_bf16, const SeqArgs &args, int MB, int S, int grid, bool cooperative,
+                                 hipStream_t s);
 
 void launch_jacobi_trace(const float *x, const float *x_ref, JacobiState st, float *delta_out, float *err_out, int B,
                          int T, int D, hipStream_t s);

@@ -720,7 +720,8 @@ static const void *pick_kernel(int MB, int S) {
     return nullptr;
 }
 
-hipError_t launch_seq_persistent(bool is_bf16, const SeqArgs &args, int MB, int S, int grid, hipStream_t s) {
+hipError_t launch_seq_persistent(bool is_bf16, const SeqArgs &args, int MB, int S, int grid, bool cooperative,
+                                 hipStream_t s) {
     const void *kern = is_bf16 ? pick_kernel<bf16>(MB, S) : pick_kernel<f16>(MB, S);
     if (!kern) return hipErrorInvalidValue;
     const size_t lds = seq_persistent_lds_bytes(MB, args.T, args.D);
@@ -728,7 +729,10 @@ hipError_t launch_seq_persistent(bool is_bf16, const SeqArgs &args, int MB, int 
     if (e != hipSuccess) return e;
     SeqArgs a = args;
     void *params[] = {&a};
-    return hipLaunchCooperativeKernel(kern, dim3(grid), dim3(P_THREADS), params, (unsigned)lds, s);
+    if (cooperative) return hipLaunchCooperativeKernel(kern, dim3(grid), dim3(P_THREADS), params, (unsigned)lds, s);
+    // plain launch: co-residency of the workgroups is then not guaranteed by the runtime; it holds when
+    // the device is otherwise idle (one workgroup per CU), and every wait in the kernel is bounded
+    return hipLaunchKernel(kern, dim3(grid), dim3(P_THREADS), params, lds, s);
 }
 
 }  // namespace sjd

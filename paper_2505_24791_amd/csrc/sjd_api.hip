@@ -77,7 +77,7 @@ struct sjd_flow {
     hipStream_t cap_stream = nullptr;
     std::map<std::tuple<int, int, const void *, const void *>, hipGraphExec_t> step_graphs;
     int use_graphs = 1;
-    int seq_path = 0;            // 0 automatic, 1 per-step launches (graph replay), 2 persistent kernel
+    int seq_path = 0;            // 0 automatic, 1 per-step launches (graph replay), 2 persistent kernel, 3 the same, plain launch
     int *psync = nullptr;        // synchronisation words of the persistent kernel (1024 ints)
     int n_cus = 0, coop = 0;
     hipEvent_t ev[SJD_MAX_BLOCKS + 1] = {};
@@ -488,7 +488,7 @@ int run_sequential_persistent(sjd_flow *f, int j, const float *z, float *x, int 
                                                steps * 4.0 * batch * (c.seq_len / 2.0) * W * c.n_layers,
                  steps * (wbytes + kvbytes), s);
     HIP_TRY(hipMemsetAsync(f->psync, 0, 1024 * sizeof(int), s));
-    hipError_t e = launch_seq_persistent(c.dtype == SJD_DTYPE_BF16, a, MB, c.width / 256, f->n_cus, s);
+    hipError_t e = launch_seq_persistent(c.dtype == SJD_DTYPE_BF16, a, MB, c.width / 256, f->n_cus, f->seq_path != 3, s);
     if (e != hipSuccess) return fail(SJD_EHIP, "persistent sequential kernel: launch failed: %s", hipGetErrorString(e));
     HIP_TRY(hipMemcpyAsync(f->host_pin, f->psync + 9, sizeof(int32_t), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
@@ -503,7 +503,7 @@ int run_sequential(sjd_flow *f, int j, const float *z, float *x, int batch, hipS
     const int T = f->cfg.seq_len, D = f->cfg.token_dim;
     const int rev = (f->cfg.reverse_mask >> j) & 1;
     if (batch == 0) return SJD_OK;
-    if (f->seq_path == 2 && !persistent_ok(f, batch))
+    if (f->seq_path >= 2 && !persistent_ok(f, batch))
         return fail(SJD_EINVAL, "the persistent sequential kernel does not cover this configuration");
     if (f->seq_path != 1 && persistent_ok(f, batch)) return run_sequential_persistent(f, j, z, x, batch, s);
     if (fast_decode_ok(f)) return run_sequential_fast(f, j, z, x, batch, s);
@@ -869,7 +869,8 @@ extern "C" __attribute__((visibility("default"))) int sjd_debug_read_sync(sjd_fl
 
 int sjd_flow_set_sequential_path(sjd_flow *f, int path) {
     if (!f) return fail(SJD_EINVAL, "null flow");
-    if (path < 0 || path > 2) return fail(SJD_EINVAL, "path must be 0 (automatic), 1 (per-step launches) or 2 (persistent kernel)");
+    if (path < 0 || path > 3)
+        return fail(SJD_EINVAL, "path must be 0 (automatic), 1 (per-step launches), 2 (persistent kernel) or 3 (the same, plain launch)");
     f->seq_path = path;
     return SJD_OK;
 }

@@ -76,5 +76,5 @@ def test_persistent_path_is_refused_outside_its_coverage(torch_cuda):
     f.set_sequential_path(0)
     assert torch.isfinite(f.sequential_inverse_block(0, z)).all()
     with pytest.raises(sjd.SjdError):
-        f.set_sequential_path(3)
+        f.set_sequential_path(4)
     f.close()
