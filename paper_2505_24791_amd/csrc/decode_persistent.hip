@@ -226,8 +226,10 @@ __device__ __forceinline__ void ln_gemm_stage(const Ctx &c_in, rsrc_t hs_rs, con
                     fa[i][s][4 * h2 + e] =
                         from_f32<HT>((xr[i][s][h2][e] - mean[i]) * rstd[i] * gr[s][h2][e] + br[s][h2][e]);
 
-    for (int cb0 = c.slot; cb0 < nbt; cb0 += P_CB * c.n) {
-        if (cb0 != c.slot) ln_prefetch<HT, S>(c, Wt, N, cb0, pre);  // later rounds: fetched here
+    // One round: the member's next (up to) P_CB column blocks.  The first round is straight-line code
+    // (its weights and biases were requested earlier), so that the waits in front of its matrix
+    // instructions cover exactly the loads they need and not the prefetches issued behind them.
+    auto round = [&](int cb0, bool first) {
         f32x4v acc[P_CB][MB];
 #pragma unroll
         for (int cc = 0; cc < P_CB; ++cc)
@@ -252,7 +254,7 @@ __device__ __forceinline__ void ln_gemm_stage(const Ctx &c_in, rsrc_t hs_rs, con
                 f32x4v t = red[q * 64 + c.lane];
 #pragma unroll
                 for (int w = 1; w < P_NW; ++w) t += red[(w * (P_CB * MB) + q) * 64 + c.lane];
-                const float bv = cb0 == c.slot ? bv0[qi] : bias[col];
+                const float bv = first ? bv0[qi] : bias[col];
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     const int row = (c.rb0 + i) * 16 + 4 * c.kg + v;
@@ -264,6 +266,11 @@ __device__ __forceinline__ void ln_gemm_stage(const Ctx &c_in, rsrc_t hs_rs, con
             }
         }
         __syncthreads();
+    };
+    round(c.slot, true);
+    for (int cb0 = c.slot + P_CB * c.n; cb0 < nbt; cb0 += P_CB * c.n) {
+        ln_prefetch<HT, S>(c, Wt, N, cb0, pre);
+        round(cb0, false);
     }
 }
 
@@ -295,24 +302,21 @@ __device__ __forceinline__ void gemm_resid_stage(const Ctx &c_in, rsrc_t a_rs, c
             const uint32_t off = (uint32_t)((((c.rb0 + i) * KSA + c.wave * KSW + u) * 64 + c.lane) * 8) * 2u;
             fa[i][u] = __builtin_bit_cast(v8, ld16_l2(a_rs, off));
         }
-    // the finishing wave (wave i for row block i) fetches its residual values and bias early
-    float rv[4] = {0.f, 0.f, 0.f, 0.f}, bv = 0.f;
-    size_t eo[4] = {0, 0, 0, 0};
+    // every wave fetches residual values and bias of the block (only waves < MB use them: no branch
+    // between the loads and the matrix instructions; rows past the workspace read as zero)
+    float rv[4], bv;
+    uint32_t eo[4];
     auto fetch_resid = [&](int cb) {
-        const int col = cb * 16 + c.r;
-        if (c.wave < MB && cb < nbt) {
+        const int cbc = cb < nbt ? cb : nbt - 1;
+        const int col = cbc * 16 + c.r;
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                eo[v] = frag_off((c.rb0 + c.wave) * 16 + 4 * c.kg + v, col, KSN);
-                rv[v] = ld4_l2(hs_rs, (uint32_t)eo[v] * 4u);
-            }
-            bv = bias[col];
+        for (int v = 0; v < 4; ++v) {
+            eo[v] = (uint32_t)frag_off((c.rb0 + c.wave) * 16 + 4 * c.kg + v, col, KSN);
+            rv[v] = ld4_l2(hs_rs, eo[v] * 4u);
         }
+        bv = bias[col];
     };
-    fetch_resid(c.slot);
-    pf();
-    for (int cb = c.slot; cb < nbt; cb += c.n) {
-        if (cb != c.slot) { res_prefetch<HT, S, KMUL>(c, Wt, cb, pre); fetch_resid(cb); }
+    auto block = [&](int cb) {
 #pragma unroll
         for (int i = 0; i < MB; ++i) {
             f32x4v acc = f32x4v{0.f, 0.f, 0.f, 0.f};
@@ -323,7 +327,7 @@ __device__ __forceinline__ void gemm_resid_stage(const Ctx &c_in, rsrc_t a_rs, c
         SJD_TLC(c);   // operands have arrived, products done
         __syncthreads();
         SJD_TLC(c);
-        if (c.wave < MB) {
+        if (c.wave < MB && cb < nbt) {
             f32x4v t = red[c.wave * 64 + c.lane];
 #pragma unroll
             for (int w = 1; w < P_NW; ++w) t += red[(w * MB + c.wave) * 64 + c.lane];
@@ -331,6 +335,14 @@ __device__ __forceinline__ void gemm_resid_stage(const Ctx &c_in, rsrc_t a_rs, c
             for (int v = 0; v < 4; ++v) hs[eo[v]] = (t[v] + bv) + rv[v];
         }
         __syncthreads();
+    };
+    fetch_resid(c.slot);
+    pf();
+    block(c.slot);                                          // straight-line first block (see ln_gemm_stage)
+    for (int cb = c.slot + c.n; cb < nbt; cb += c.n) {
+        res_prefetch<HT, S, KMUL>(c, Wt, cb, pre);
+        fetch_resid(cb);
+        block(cb);
     }
 }
 
@@ -389,9 +401,9 @@ __device__ __forceinline__ void attention_stage(const Ctx &c_in, rsrc_t qkv_rs, 
         };
         const v8 kfresh = chunk(1, dc), vfresh = chunk(2, dc), q8 = chunk(0, dc);
         const size_t cbase = ((size_t)b * T) * W + h * 64;
-        if (valid) {
-            if (stid < 8) *reinterpret_cast<v8 *>(kc + cbase + (size_t)t * W + stid * 8) = chunk(1, stid);
-            else if (stid < 16) *reinterpret_cast<v8 *>(vc + cbase + (size_t)t * W + (stid - 8) * 8) = chunk(2, stid - 8);
+        if (valid && stid < 16) {   // threads 0..7 hold the fresh k chunks, 8..15 the fresh v chunks (dc = stid & 7)
+            HT *dst = (stid < 8 ? kc : vc) + cbase + (size_t)t * W + dc * 8;
+            *reinterpret_cast<v8 *>(dst) = stid < 8 ? kfresh : vfresh;
         }
         float qf[8];
 #pragma unroll
