@@ -361,7 +361,8 @@ static void pick_tile(const HT *A, const HT *Bt, const float *bias, const float 
     const long t256 = (long)((M + 255) / 256) * ((N + 255) / 256);
     const bool deep = K >= 3072 || (EPI == EPI_BIAS && K >= 768 && N >= 768);
     if (deep && M >= 256 && N >= 256 && t256 >= 256) launch_dma<HT, OutT, EPI>(A, Bt, bias, resid, C, M, N, K, s);
-    else if (N >= 128 && M >= 256 && t128 >= 512) launch_tile<HT, 256, 128, 32, 2, OutT, EPI>(A, Bt, bias, resid, C, M, N, K, s);
+    // measured: below ~3500 tiles of 128x128 the smaller tile wins (finer tail, shorter prologue per tile)
+    else if (N >= 128 && M >= 256 && t128 >= 3584) launch_tile<HT, 256, 128, 32, 2, OutT, EPI>(A, Bt, bias, resid, C, M, N, K, s);
     else launch_tile<HT, 128, 128, 64, 1, OutT, EPI>(A, Bt, bias, resid, C, M, N, K, s);
 }
 
