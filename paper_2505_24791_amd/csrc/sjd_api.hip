@@ -505,7 +505,11 @@ int run_sequential(sjd_flow *f, int j, const float *z, float *x, int batch, hipS
     if (batch == 0) return SJD_OK;
     if (f->seq_path >= 2 && !persistent_ok(f, batch))
         return fail(SJD_EINVAL, "the persistent sequential kernel does not cover this configuration");
-    if (f->seq_path != 1 && persistent_ok(f, batch)) return run_sequential_persistent(f, j, z, x, batch, s);
+    // automatic choice: the persistent kernel, except for long sequences at the largest width, where its
+    // attention stage (two pairs at a time per CU) and the eightfold weight traffic lose to per-step launches
+    // (measured: T = 1024, W = 1024, 32 samples: 541 ms against 505 ms)
+    const bool prefer_steps = f->seq_path == 0 && f->cfg.seq_len > 512 && f->cfg.width >= 1024;
+    if (f->seq_path != 1 && !prefer_steps && persistent_ok(f, batch)) return run_sequential_persistent(f, j, z, x, batch, s);
     if (fast_decode_ok(f)) return run_sequential_fast(f, j, z, x, batch, s);
     launch_decode_epilogue(f->p, z, x, batch, T, D, -1, rev, s);  // x_1 = y_1
     for (int t = 0; t + 1 < T; ++t) decode_step(f, j, z, x, batch, t, s);
