@@ -216,3 +216,38 @@ def test_config2_subset_matches_oracle(torch_cuda, orc32):
     assert err <= TOL_BF16
     assert np.abs(iters.astype(int) - riters).max() <= 1
     f.close()
+
+
+def test_config2_full_batch_sampled_outputs_match_oracle(torch_cuda, orc32):
+    """Configuration 2 exactly as `bench.py` launches it (batch 64, selective strategy, default
+    options): the oracle recomputes a spread of samples one by one (samples are independent), and
+    properties that hold for every sample are checked on all of them."""
+    import paper_2505_24791_amd as sjd
+    torch = torch_cuda
+    cfg = wl.CONFIGS["C2"]
+    blob = wl.make_weights(cfg)
+    z = wl.make_latent(cfg)
+    f = _flow(cfg, blob)
+    mask = ~1 & ((1 << cfg.n_blocks) - 1)
+    zd = _dev(torch, z)
+    x, stats, iters = f.sample(zd, mask, sjd.JacobiOpts(tau=cfg.tau))
+    xs = x.cpu().numpy()
+    picks = [0, 9, 26, 47, 63]
+    rx, riters, _ = orc32.sample(cfg, blob, z[picks], mask, cfg.tau)
+    err = np.abs(xs[picks] - rx).max()
+    print(f"C2 full batch: max err on samples {picks}: {err:.3e}; passes {stats['block_iters']}")
+    assert err <= TOL_BF16
+    assert np.abs(iters[:, picks].astype(int) - riters).max() <= 1
+    # every sample: finite, block 0 took T-1 steps, Jacobi blocks between 2 passes and the cap, and the
+    # forward map takes the result back to the latent (Jacobi blocks stopped at tau, so to within a few tau)
+    assert np.isfinite(xs).all()
+    assert (iters[0] == cfg.seq_len - 1).all()
+    assert (iters[1:] >= 2).all() and (iters[1:] <= cfg.seq_len).all()
+    zz, logdet = f.forward(x)
+    assert (zz - zd).abs().max().item() <= 0.1
+    assert (zz - zd).abs().mean().item() <= 5 * cfg.tau
+    assert torch.isfinite(logdet).all()
+    # a second run gives the same bits
+    x2, _, iters2 = f.sample(zd, mask, sjd.JacobiOpts(tau=cfg.tau))
+    assert torch.equal(x, x2) and np.array_equal(iters, iters2)
+    f.close()
