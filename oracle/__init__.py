@@ -18,12 +18,12 @@ from . import build as _build
 class _Cfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
                 ("n_blocks", "n_layers", "width", "n_heads", "mlp_ratio", "seq_len", "token_dim")] + \
-               [("reverse_mask", C.c_uint32)]
+               [("reverse_mask", C.c_uint32), ("mask_nearest", C.c_int32)]
 
 
 def _as_cfg(cfg) -> _Cfg:
     return _Cfg(cfg.n_blocks, cfg.n_layers, cfg.width, cfg.n_heads, cfg.mlp_ratio, cfg.seq_len,
-                cfg.token_dim, cfg.reverse_mask)
+                cfg.token_dim, cfg.reverse_mask, int(getattr(cfg, "mask_nearest", 0)))
 
 
 class Oracle:

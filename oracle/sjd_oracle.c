@@ -61,6 +61,7 @@ typedef REAL real;
 typedef struct {
     int32_t n_blocks, n_layers, width, n_heads, mlp_ratio, seq_len, token_dim;
     uint32_t reverse_mask;
+    int32_t mask_nearest; /* o of eq. 6: the attention of position t sees keys 0..t-o only (0: plain causal) */
 } orc_config;
 
 typedef struct {
@@ -139,9 +140,12 @@ static real gelu_erf(real v) {
 }
 
 /* Causal attention for one query row: head h of q attends keys/values of rows 0..t (inclusive).
- * Kc, Vc are [T][W] with head h in columns h*dh..; scores scratch holds t+1 reals. */
+ * Kc, Vc are [T][W] with head h in columns h*dh..; scores scratch holds t+1 reals.
+ * A row that sees no key at all (t < 0, which only the masked variant of eq. 6 produces) gets a
+ * zero attention output. */
 static void attend_row(const real *q, const real *Kc, const real *Vc, int t, int W, int H, real *o, real *scores) {
     int dh = W / H;
+    if (t < 0) { for (int i = 0; i < W; ++i) o[i] = 0; return; }
     real scale = (real)(1.0 / sqrt((double)dh));
     for (int h = 0; h < H; ++h) {
         const real *qh = q + h * dh;
@@ -222,7 +226,7 @@ static void cond_full(const orc_config *c, const block_w *bw, const real *x, con
             memcpy(Vc + (size_t)t * W, r + 2 * W, sizeof(real) * W);
         }
         for (int t = 0; t < T; ++t)
-            attend_row(w->q + (size_t)t * W, Kc, Vc, t, W, H, w->a + (size_t)t * W, w->scores);
+            attend_row(w->q + (size_t)t * W, Kc, Vc, t - c->mask_nearest, W, H, w->a + (size_t)t * W, w->scores);
         for (int t = 0; t < T; ++t) {
             real *ht = w->h + (size_t)t * W;
             linear_row(w->a + (size_t)t * W, lw->w_o, lw->b_o, W, W, w->t1);
@@ -260,7 +264,7 @@ static void cond_step(const orc_config *c, const block_w *bw, const real *xt, in
         linear_row(a, lw->w_qkv, lw->b_qkv, W, 3 * W, r);
         memcpy(Kc + (size_t)t * W, r + W, sizeof(real) * W);
         memcpy(Vc + (size_t)t * W, r + 2 * W, sizeof(real) * W);
-        attend_row(r, Kc, Vc, t, W, H, a, w->scores);
+        attend_row(r, Kc, Vc, t - c->mask_nearest, W, H, a, w->scores);
         linear_row(a, lw->w_o, lw->b_o, W, W, w->t1);
         for (int i = 0; i < W; ++i) h[i] += w->t1[i];
         layernorm_row(h, lw->ln2_g, lw->ln2_b, W, a);

@@ -366,3 +366,62 @@ def test_logdet_closed_forms(orc64, orc32):
     z, ld = orc64.forward_logdet(cfg, blob, x)
     np.testing.assert_array_equal(ld, [0.0, 0.0])
     np.testing.assert_array_equal(z, x.astype(np.float64))
+
+
+# ---- masked-dependency probe (eq. 6): attention without the o nearest predecessors ---------------
+
+def _masked(cfg, o):
+    return cfg.with_(mask_nearest=o)
+
+
+def test_masked_probe_zero_offset_is_the_plain_model(orc64):
+    cfg, blob, z = _flow(6, seed=9)
+    for j in range(cfg.n_blocks):
+        np.testing.assert_array_equal(orc64.sequential_inverse_block(_masked(cfg, 0), blob, j, z[0]),
+                                      orc64.sequential_inverse_block(cfg, blob, j, z[0]))
+
+
+@pytest.mark.parametrize("o", [1, 2, 4])
+def test_masked_probe_dependency_structure(orc64, o):
+    """With the o nearest predecessors masked, the parameters of token l (head row l-1) come from
+    token l-1 itself (residual path) and from tokens <= l-1-o (attention): changing token j must
+    leave rows q with j < q < j+o bit-identical and change row j and rows q >= j+o."""
+    T = 9
+    cfg, blob, z = _flow(T, seed=4, K=1)
+    cfg = _masked(cfg, o)
+    x = z[0].astype(np.float64)
+    mu0, al0 = orc64.cond(cfg, blob, 0, x)                 # row l: parameters of token l (from head row l-1)
+    for j in range(T - 1):
+        xp = x.copy(); xp[j] += 0.37
+        mu1, al1 = orc64.cond(cfg, blob, 0, xp)
+        changed = [l for l in range(T) if not (np.array_equal(mu0[l], mu1[l]) and np.array_equal(al0[l], al1[l]))]
+        # head row q = l-1 depends on token q and tokens <= q-o
+        expect = [l for l in range(1, T) if (l - 1 == j) or (l - 1 - o >= j)]
+        assert changed == expect, (o, j, changed, expect)
+
+
+def test_masked_probe_with_everything_masked_equals_no_attention(orc64):
+    """o >= T: no row sees any key, attention contributes only its output bias - the same map as
+    the plain model with the attention output projection set to zero."""
+    T = 7
+    cfg, blob, z = _flow(T, seed=6)
+    blob0 = blob.copy()
+    for v in wl.blob_views(cfg, blob0):
+        for l in range(cfg.n_layers):
+            v[f"l{l}.w_o"][...] = 0.0
+    for j in range(cfg.n_blocks):
+        a = orc64.sequential_inverse_block(_masked(cfg, T), blob, j, z[0])
+        b = orc64.sequential_inverse_block(cfg, blob0, j, z[0])
+        np.testing.assert_allclose(a, b, atol=1e-13)
+        # and Jacobi decoding of the masked model reaches the masked sequential result (same triangular structure)
+        xj, it = orc64.jacobi_inverse_block(_masked(cfg, 2), blob, j, z[0], 0.0)
+        np.testing.assert_allclose(xj, orc64.sequential_inverse_block(_masked(cfg, 2), blob, j, z[0]), atol=1e-11)
+
+
+def test_masked_probe_forward_inverts_masked_inverse(orc64):
+    cfg, blob, z = _flow(8, seed=2)
+    cfg = _masked(cfg, 3)
+    for j in range(cfg.n_blocks):
+        x = orc64.sequential_inverse_block(cfg, blob, j, z[0])
+        np.testing.assert_allclose(orc64.forward_block(cfg, blob, j, x), z[0], atol=1e-12)
+        np.testing.assert_allclose(orc64.sequential_inverse_block_naive(cfg, blob, j, z[0]), x, atol=1e-12)

@@ -54,6 +54,7 @@ class FlowConfig:
     mlp_ratio: int = 4
     tau: float = 1e-3
     temperature: float = 1.0
+    mask_nearest: int = 0   # o of the masked-dependency probe (eq. 6): attention skips the o nearest predecessors
 
     @property
     def head_dim(self) -> int:
