@@ -193,6 +193,13 @@ SJD_API int sjd_conditioner(sjd_flow *flow, int block, const float *x_dev, float
 SJD_API int sjd_op_linear_h16(int dtype, int kernel, const void *a_dev, const void *wt_dev, const float *bias_dev,
                               float *resid_out_dev, void *c_dev, int M, int N, int K, int epilogue, void *hip_stream);
 
+/* The masked-dependency probe of Sec. 3.2, eq. 6: with o > 0 every attention of the conditioner ignores
+ * the o nearest preceding positions (position p sees keys 0..p-o; a position that sees no key gets a
+ * zero attention output), in every call of this flow (sequential, Jacobi, conditioner, forward).
+ * o = 0 (the default) is the model itself.  A diagnostic: it runs on the row-wise attention kernel and
+ * plain per-step launches, not on the tuned paths.  0 <= o <= T, else SJD_EINVAL. */
+SJD_API int sjd_flow_set_mask_nearest(sjd_flow *flow, int o);
+
 /* How sjd_sequential_inverse_block (and the sequential blocks of sjd_sample) run in the 16-bit modes:
  * 0 automatic (the persistent kernel where it applies, else per-step launches), 1 per-step launches
  * replayed as a graph, 2 the persistent kernel (SJD_EINVAL at the call if the configuration is outside

@@ -14,7 +14,8 @@ namespace sjd {
 // ------------------------------------------------------------------------------------------------
 // Row-wise kernel.  Keys 0..n_cached-1 come from the cache; if `fresh` is set the query's own
 // position (key n_cached) comes from the row just computed, and that row's k, v are also written
-// into the cache at position n_cached.
+// into the cache at position n_cached.  mask_o > 0: the masked-dependency probe of eq. 6, the query
+// at position p sees keys 0..p-mask_o only; a row that sees no key gets a zero output.
 template <typename QT, typename KVT>
 __global__ __launch_bounds__(256) void attention_rows_kernel(const QT *__restrict__ q, int64_t q_stride,
                                                              const KVT *k, const KVT *v, int64_t kv_stride,
@@ -22,7 +23,7 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const QT *__restric
                                                              const QT *__restrict__ vfresh, KVT *kstore, KVT *vstore,
                                                              QT *__restrict__ o, int64_t o_stride, int n_work,
                                                              int q_rows_per_sample, int t0, int H, int dh,
-                                                             int max_keys) {
+                                                             int max_keys, int mask_o) {
     extern __shared__ float smem[];
     const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int w = blockIdx.x * 4 + wv;
@@ -33,8 +34,10 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const QT *__restric
     const int h = (w / q_rows_per_sample) % H;
     const int i = w / (q_rows_per_sample * H);
     const int64_t qrow = (int64_t)i * q_rows_per_sample + r;
-    const int n_cached = kfresh ? t0 + r : t0 + r + 1;
-    const int n_keys = t0 + r + 1;
+    const int own = t0 + r;                                   // the query's position
+    const int n_keys = own + 1 - mask_o > 0 ? own + 1 - mask_o : 0;
+    const int fresh_at = kfresh ? own : own + 1;              // cache rows below this index are valid
+    const int n_cached = n_keys < fresh_at ? n_keys : fresh_at;
     const QT *qp = q + qrow * q_stride + h * dh;
     for (int d = lane; d < dh; d += 64) qs[d] = to_f32<QT>(qp[d]);
     const KVT *kb = k + (int64_t)i * kv_sample_stride + h * dh;
@@ -42,8 +45,8 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const QT *__restric
     const QT *kf = kfresh ? kfresh + qrow * q_stride + h * dh : nullptr;
     const QT *vf = vfresh ? vfresh + qrow * q_stride + h * dh : nullptr;
     if (kf) {
-        KVT *ks = kstore + (int64_t)i * kv_sample_stride + (int64_t)n_cached * kv_stride + h * dh;
-        KVT *vs = vstore + (int64_t)i * kv_sample_stride + (int64_t)n_cached * kv_stride + h * dh;
+        KVT *ks = kstore + (int64_t)i * kv_sample_stride + (int64_t)own * kv_stride + h * dh;
+        KVT *vs = vstore + (int64_t)i * kv_sample_stride + (int64_t)own * kv_stride + h * dh;
         for (int d = lane; d < dh; d += 64) {
             ks[d] = from_f32<KVT>(to_f32<QT>(kf[d]));
             vs[d] = from_f32<KVT>(to_f32<QT>(vf[d]));
@@ -75,7 +78,7 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const QT *__restric
     den = wave_sum(den);
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_s_waitcnt(0xc07f);
-    const float inv = 1.0f / den;
+    const float inv = n_keys > 0 ? 1.0f / den : 0.f;
     for (int d = lane; d < dh; d += 64) {
         float acc = 0.f;
         for (int s = 0; s < n_cached; ++s) acc = fmaf(sc[s], to_f32<KVT>(vb[(int64_t)s * kv_stride + d]), acc);
@@ -87,25 +90,25 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const QT *__restric
 template <typename QT, typename KVT>
 void launch_attention_rows(const QT *q, int64_t q_stride, const KVT *k, const KVT *v, int64_t kv_stride,
                            int64_t kv_sample_stride, QT *o, int64_t o_stride, int n_samples, int q_rows_per_sample,
-                           int t0, int H, int dh, hipStream_t s) {
+                           int t0, int H, int dh, int mask_o, hipStream_t s) {
     const int n_work = n_samples * H * q_rows_per_sample;
     if (n_work <= 0) return;
     const int max_keys = t0 + q_rows_per_sample;
     const size_t smem = 4 * (size_t)(dh + max_keys) * sizeof(float);
     hipLaunchKernelGGL((attention_rows_kernel<QT, KVT>), dim3((n_work + 3) / 4), dim3(256), smem, s, q, q_stride, k, v,
                        kv_stride, kv_sample_stride, (const QT *)nullptr, (const QT *)nullptr, (KVT *)nullptr,
-                       (KVT *)nullptr, o, o_stride, n_work, q_rows_per_sample, t0, H, dh, max_keys);
+                       (KVT *)nullptr, o, o_stride, n_work, q_rows_per_sample, t0, H, dh, max_keys, mask_o);
 }
 template void launch_attention_rows<float, float>(const float *, int64_t, const float *, const float *, int64_t,
-                                                  int64_t, float *, int64_t, int, int, int, int, int, hipStream_t);
+                                                  int64_t, float *, int64_t, int, int, int, int, int, int, hipStream_t);
 template void launch_attention_rows<bf16, bf16>(const bf16 *, int64_t, const bf16 *, const bf16 *, int64_t, int64_t,
-                                                bf16 *, int64_t, int, int, int, int, int, hipStream_t);
+                                                bf16 *, int64_t, int, int, int, int, int, int, hipStream_t);
 template void launch_attention_rows<f16, f16>(const f16 *, int64_t, const f16 *, const f16 *, int64_t, int64_t, f16 *,
-                                              int64_t, int, int, int, int, int, hipStream_t);
+                                              int64_t, int, int, int, int, int, int, hipStream_t);
 
 template <typename AT>
 void launch_decode_attention(const AT *qkv, AT *kcache, AT *vcache, AT *o, int B, int T, int t, int H, int dh,
-                             hipStream_t s) {
+                             int mask_o, hipStream_t s) {
     const int n_work = B * H;
     if (n_work <= 0) return;
     const int W = H * dh;
@@ -113,12 +116,13 @@ void launch_decode_attention(const AT *qkv, AT *kcache, AT *vcache, AT *o, int B
     const size_t smem = 4 * (size_t)(dh + max_keys) * sizeof(float);
     hipLaunchKernelGGL((attention_rows_kernel<AT, AT>), dim3((n_work + 3) / 4), dim3(256), smem, s, qkv,
                        (int64_t)3 * W, (const AT *)kcache, (const AT *)vcache, (int64_t)W, (int64_t)T * W,
-                       qkv + W, qkv + 2 * W, kcache, vcache, o, (int64_t)W, n_work, 1, t, H, dh, max_keys);
+                       qkv + W, qkv + 2 * W, kcache, vcache, o, (int64_t)W, n_work, 1, t, H, dh, max_keys, mask_o);
 }
-template void launch_decode_attention<float>(const float *, float *, float *, float *, int, int, int, int, int,
+template void launch_decode_attention<float>(const float *, float *, float *, float *, int, int, int, int, int, int,
                                              hipStream_t);
-template void launch_decode_attention<bf16>(const bf16 *, bf16 *, bf16 *, bf16 *, int, int, int, int, int, hipStream_t);
-template void launch_decode_attention<f16>(const f16 *, f16 *, f16 *, f16 *, int, int, int, int, int, hipStream_t);
+template void launch_decode_attention<bf16>(const bf16 *, bf16 *, bf16 *, bf16 *, int, int, int, int, int, int,
+                                            hipStream_t);
+template void launch_decode_attention<f16>(const f16 *, f16 *, f16 *, f16 *, int, int, int, int, int, int, hipStream_t);
 
 // ------------------------------------------------------------------------------------------------
 // Flash-style kernel, head size 64.  A workgroup (4 waves) owns 128 query rows of one

@@ -134,18 +134,18 @@ void launch_gemm_h16(const HT *A, const HT *Bt, const float *bias, const float *
 
 // Causal attention, one wave per (sample, head, query row); works for any shape and both types.
 // q rows: q + (sample*q_rows_per_sample + r) * q_stride; row r (processing position t0 + r) attends
-// keys 0..t0+r found at k + sample_index*kv_sample_stride + key*kv_stride (+ head*dh); same for v.
+// keys 0..t0+r-mask_o found at k + sample_index*kv_sample_stride + key*kv_stride (+ head*dh); same for v.
 // kv_index: nullptr => sample i uses cache slot i, else slot kv_index[i].
 template <typename QT, typename KVT>
 void launch_attention_rows(const QT *q, int64_t q_stride, const KVT *k, const KVT *v, int64_t kv_stride,
                            int64_t kv_sample_stride, QT *o, int64_t o_stride, int n_samples, int q_rows_per_sample,
-                           int t0, int H, int dh, hipStream_t s);
+                           int t0, int H, int dh, int mask_o, hipStream_t s);
 
 // Single-token step: writes this step's k, v (from the fused qkv row) into the cache at position t,
 // then attends keys 0..t.  qkv [B, 3W], cache [B, T, W] each for k and v, o [B, W].
 template <typename AT>
 void launch_decode_attention(const AT *qkv, AT *kcache, AT *vcache, AT *o, int B, int T, int t, int H, int dh,
-                             hipStream_t s);
+                             int mask_o, hipStream_t s);
 
 // Flash-style causal attention on 16-bit qkv [n_samples*T, 3W] (head size 64), o [n_samples*T, W].
 template <typename HT>

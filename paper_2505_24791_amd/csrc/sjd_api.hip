@@ -77,6 +77,7 @@ struct sjd_flow {
     hipStream_t cap_stream = nullptr;
     std::map<std::tuple<int, int, const void *, const void *>, hipGraphExec_t> step_graphs;
     int use_graphs = 1;
+    int mask_nearest = 0;        // o of the masked-dependency probe (eq. 6); 0: plain causal attention
     int seq_path = 0;            // 0 automatic, 1 per-step launches (graph replay), 2 persistent kernel, 3 the same, plain launch
     int *psync = nullptr;        // synchronisation words of the persistent kernel (1024 ints)
     int n_cus = 0, coop = 0;
@@ -193,12 +194,14 @@ void layernorm(sjd_flow *f, const float *x, const float *g, const float *b, void
 
 // whole-sequence causal attention on the fused qkv buffer [n*T, 3W] -> o [n*T, W]
 template <typename AT>
-void attention_full(const void *qkv, void *o, int n, int T, int W, int H, hipStream_t s) {
+void attention_full(const void *qkv, void *o, int n, int T, int W, int H, int mask_o, hipStream_t s) {
     const AT *q = (const AT *)qkv;
     if constexpr (sizeof(AT) == 2) {
-        if (W / H == 64) { launch_flash_attention_h16<AT>(q, (AT *)o, n, T, H, s); return; }
+        if (W / H == 64 && mask_o == 0) { launch_flash_attention_h16<AT>(q, (AT *)o, n, T, H, s); return; }
     }
-    launch_attention_rows<AT, AT>(q, 3 * W, q + W, q + 2 * W, 3 * W, (int64_t)T * 3 * W, (AT *)o, W, n, T, 0, H, W / H, s);
+    // the masked probe (a diagnostic) takes the row-wise kernel in every mode
+    launch_attention_rows<AT, AT>(q, 3 * W, q + W, q + 2 * W, 3 * W, (int64_t)T * 3 * W, (AT *)o, W, n, T, 0, H, W / H,
+                                  mask_o, s);
 }
 
 template <typename AT>
@@ -206,7 +209,7 @@ void attention_step(sjd_flow *f, int l, int B, int t, hipStream_t s) {
     const sjd_config &c = f->cfg;
     const size_t layer_off = (size_t)l * c.max_batch * c.seq_len * c.width;
     launch_decode_attention<AT>((const AT *)f->qkv, (AT *)f->kcache + layer_off, (AT *)f->vcache + layer_off,
-                                (AT *)f->o, B, c.seq_len, t, c.n_heads, c.width / c.n_heads, s);
+                                (AT *)f->o, B, c.seq_len, t, c.n_heads, c.width / c.n_heads, f->mask_nearest, s);
 }
 
 // Whole-sequence conditioner pass on `n` samples listed in `active` (device, nullable = identity).
@@ -228,9 +231,9 @@ void conditioner_pass(sjd_flow *f, int j, const float *x, int n, const int32_t *
         {
             const double ab = act_bytes(f);
             ProfScope ps(f, SJD_PROF_ATTENTION, 2.0 * n * (double)T * (T + 1) * W, (double)M * 4 * W * ab, s);
-            if (c.dtype == SJD_DTYPE_BF16) attention_full<bf16>(f->qkv, f->o, n, T, W, H, s);
-            else if (c.dtype == SJD_DTYPE_F16) attention_full<f16>(f->qkv, f->o, n, T, W, H, s);
-            else attention_full<float>(f->qkv, f->o, n, T, W, H, s);
+            if (c.dtype == SJD_DTYPE_BF16) attention_full<bf16>(f->qkv, f->o, n, T, W, H, f->mask_nearest, s);
+            else if (c.dtype == SJD_DTYPE_F16) attention_full<f16>(f->qkv, f->o, n, T, W, H, f->mask_nearest, s);
+            else attention_full<float>(f->qkv, f->o, n, T, W, H, f->mask_nearest, s);
         }
         project(f, SJD_PROF_GEMM, f->o, lw.w_o, lw.t_o, lw.b_o, f->h, M, W, W, EPI_BIAS_RESIDUAL, true, s);
         layernorm(f, f->h, lw.ln2_g, lw.ln2_b, f->a, M, s);
@@ -503,14 +506,17 @@ int run_sequential(sjd_flow *f, int j, const float *z, float *x, int batch, hipS
     const int T = f->cfg.seq_len, D = f->cfg.token_dim;
     const int rev = (f->cfg.reverse_mask >> j) & 1;
     if (batch == 0) return SJD_OK;
-    if (f->seq_path >= 2 && !persistent_ok(f, batch))
-        return fail(SJD_EINVAL, "the persistent sequential kernel does not cover this configuration");
-    // automatic choice: the persistent kernel, except for long sequences at the largest width, where its
-    // attention stage (two pairs at a time per CU) and the eightfold weight traffic lose to per-step launches
-    // (measured: T = 1024, W = 1024, 32 samples: 541 ms against 505 ms)
-    const bool prefer_steps = f->seq_path == 0 && f->cfg.seq_len > 512 && f->cfg.width >= 1024;
-    if (f->seq_path != 1 && !prefer_steps && persistent_ok(f, batch)) return run_sequential_persistent(f, j, z, x, batch, s);
-    if (fast_decode_ok(f)) return run_sequential_fast(f, j, z, x, batch, s);
+    if (f->mask_nearest == 0) {   // the masked probe takes the plain per-step path below in every mode
+        if (f->seq_path >= 2 && !persistent_ok(f, batch))
+            return fail(SJD_EINVAL, "the persistent sequential kernel does not cover this configuration");
+        // automatic choice: the persistent kernel, except for long sequences at the largest width, where its
+        // attention stage (two pairs at a time per CU) and the eightfold weight traffic lose to per-step
+        // launches (measured: T = 1024, W = 1024, 32 samples: 541 ms against 505 ms)
+        const bool prefer_steps = f->seq_path == 0 && f->cfg.seq_len > 512 && f->cfg.width >= 1024;
+        if (f->seq_path != 1 && !prefer_steps && persistent_ok(f, batch))
+            return run_sequential_persistent(f, j, z, x, batch, s);
+        if (fast_decode_ok(f)) return run_sequential_fast(f, j, z, x, batch, s);
+    }
     launch_decode_epilogue(f->p, z, x, batch, T, D, -1, rev, s);  // x_1 = y_1
     for (int t = 0; t + 1 < T; ++t) decode_step(f, j, z, x, batch, t, s);
     HIP_TRY(hipGetLastError());
@@ -870,6 +876,13 @@ extern "C" __attribute__((visibility("default"))) int sjd_debug_read_sync(sjd_fl
     return hipMemcpy(out1024, f->psync, 1024 * sizeof(int), hipMemcpyDeviceToHost) == hipSuccess ? 0 : -1;
 }
 #endif
+
+int sjd_flow_set_mask_nearest(sjd_flow *f, int o) {
+    if (!f) return fail(SJD_EINVAL, "null flow");
+    if (o < 0 || o > f->cfg.seq_len) return fail(SJD_EINVAL, "the mask offset must lie in 0..T");
+    f->mask_nearest = o;
+    return SJD_OK;
+}
 
 int sjd_flow_set_sequential_path(sjd_flow *f, int path) {
     if (!f) return fail(SJD_EINVAL, "null flow");
