@@ -7,30 +7,48 @@ namespace sjd {
 
 // ------------------------------------------------------------------------------------------------
 // Embedding: h[m, :] = x[b, tok, :] * w_in + b_in + pos[p, :]   (p = processing position of row m)
-// One workgroup per row; D is small (tens), W up to a few thousand.
+// A workgroup handles EMB_ROWS rows: a thread keeps its columns of w_in in registers across the
+// rows (D is small, tens; W up to a few thousand), so w_in is read from L2 once per EMB_ROWS rows.
+constexpr int EMB_ROWS = 16;
 __global__ __launch_bounds__(256) void embed_kernel(const float *__restrict__ x, const float *__restrict__ w_in,
                                                     const float *__restrict__ b_in, const float *__restrict__ pos,
-                                                    float *__restrict__ h, int D, int W, RowMap map) {
-    extern __shared__ float xs[];
-    const int m = blockIdx.x;
-    const int i = m / map.rows_per_sample;
-    const int p = map.t0 + m % map.rows_per_sample;
-    const int b = map.active ? map.active[i] : i;
-    const int tok = map.reversed ? map.T - 1 - p : p;
-    const float *xr = x + ((size_t)b * map.T + tok) * D;
-    for (int d = threadIdx.x; d < D; d += blockDim.x) xs[d] = xr[d];
+                                                    float *__restrict__ h, int n_rows, int D, int W, RowMap map) {
+    extern __shared__ float xs[];   // [EMB_ROWS][D]
+    __shared__ int prow[EMB_ROWS];
+    const int m0 = blockIdx.x * EMB_ROWS;
+    const int rows = n_rows - m0 < EMB_ROWS ? n_rows - m0 : EMB_ROWS;
+    for (int e = threadIdx.x; e < rows * D; e += 256) {
+        const int r = e / D, d = e - r * D;
+        const int m = m0 + r;
+        const int i = m / map.rows_per_sample;
+        const int p = map.t0 + m % map.rows_per_sample;
+        const int b = map.active ? map.active[i] : i;
+        const int tok = map.reversed ? map.T - 1 - p : p;
+        xs[e] = x[((size_t)b * map.T + tok) * D + d];
+        if (d == 0) prow[r] = p;
+    }
     __syncthreads();
-    for (int w = threadIdx.x; w < W; w += blockDim.x) {
-        float acc = b_in[w];
-        for (int d = 0; d < D; ++d) acc = fmaf(xs[d], w_in[(size_t)d * W + w], acc);
-        h[(size_t)m * W + w] = acc + pos[(size_t)p * W + w];
+    for (int w = threadIdx.x; w < W; w += 256) {
+        float acc[EMB_ROWS];
+        const float bias = b_in[w];
+#pragma unroll
+        for (int r = 0; r < EMB_ROWS; ++r) acc[r] = bias;
+        for (int d = 0; d < D; ++d) {
+            const float wv = w_in[(size_t)d * W + w];
+#pragma unroll
+            for (int r = 0; r < EMB_ROWS; ++r) acc[r] = fmaf(r < rows ? xs[r * D + d] : 0.f, wv, acc[r]);
+        }
+#pragma unroll
+        for (int r = 0; r < EMB_ROWS; ++r)
+            if (r < rows) h[(size_t)(m0 + r) * W + w] = acc[r] + pos[(size_t)prow[r] * W + w];
     }
 }
 
 void launch_embed(const float *x, const float *w_in, const float *b_in, const float *pos, float *h, int n_rows, int D,
                   int W, RowMap map, hipStream_t s) {
     if (n_rows <= 0) return;
-    hipLaunchKernelGGL(embed_kernel, dim3(n_rows), dim3(256), D * sizeof(float), s, x, w_in, b_in, pos, h, D, W, map);
+    hipLaunchKernelGGL(embed_kernel, dim3((n_rows + EMB_ROWS - 1) / EMB_ROWS), dim3(256), EMB_ROWS * D * sizeof(float), s, x,
+                       w_in, b_in, pos, h, n_rows, D, W, map);
 }
 
 // ------------------------------------------------------------------------------------------------
