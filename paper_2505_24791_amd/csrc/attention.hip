@@ -167,6 +167,22 @@ __global__ __launch_bounds__(256) void flash_attention_h16_kernel(const HT *__re
 
     const int last_row = min(qt * FA_BQ + FA_BQ - 1, T - 1);
     const int n_kt = last_row / FA_BK + 1;
+    // K/V tiles go global -> registers -> LDS; the registers of tile kt+1 are requested before tile kt is
+    // used, so that their latency hides behind the matrix instructions of tile kt.
+    v8 kreg[2], vreg[2];
+    auto fetch_tile = [&](int kt_) {
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const int c = tid + r * 256;
+            const int key = c >> 3, dc = c & 7;
+            int krow = kt_ * FA_BK + key;
+            krow = krow < T ? krow : T - 1;
+            const HT *src = base + (size_t)krow * 3 * W + h * FA_DH + dc * 8;
+            kreg[r] = *reinterpret_cast<const v8 *>(src + W);
+            vreg[r] = *reinterpret_cast<const v8 *>(src + 2 * W);
+        }
+    };
+    fetch_tile(0);
     for (int kt = 0; kt < n_kt; ++kt) {
         const int key0 = kt * FA_BK;
         __syncthreads();  // previous tile fully consumed
@@ -175,16 +191,12 @@ __global__ __launch_bounds__(256) void flash_attention_h16_kernel(const HT *__re
         for (int r = 0; r < 2; ++r) {
             const int c = tid + r * 256;
             const int key = c >> 3, dc = c & 7;
-            int krow = key0 + key;
-            krow = krow < T ? krow : T - 1;
-            const HT *src = base + (size_t)krow * 3 * W + h * FA_DH + dc * 8;
-            const v8 kv8 = *reinterpret_cast<const v8 *>(src + W);
-            const v8 vv8 = *reinterpret_cast<const v8 *>(src + 2 * W);
-            *reinterpret_cast<v8 *>(&Ks[key * FA_KS + dc * 8]) = kv8;
+            *reinterpret_cast<v8 *>(&Ks[key * FA_KS + dc * 8]) = kreg[r];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) Vt[(dc * 8 + e) * FA_VS + key] = vv8[e];
+            for (int e = 0; e < 8; ++e) Vt[(dc * 8 + e) * FA_VS + key] = vreg[r][e];
         }
         __syncthreads();
+        if (kt + 1 < n_kt) fetch_tile(kt + 1);
         if (key0 > q0 + 31) continue;  // tile lies entirely above this wave's rows (wave-uniform)
 
         // S^T = K Q^T : two 32-key blocks
