@@ -131,11 +131,16 @@ template void launch_decode_attention<f16>(const f16 *, f16 *, f16 *, f16 *, int
 // lane-local plus one cross-half exchange, and the probabilities are already laid out as the
 // B operand of the second product O^T = V^T P^T (16 keys per instruction).
 constexpr int FA_BQ = 128, FA_BK = 64, FA_DH = 64;
-constexpr int FA_KS = FA_DH + 8;   // K tile row stride (elements)
-constexpr int FA_VS = FA_BK + 8;   // V^T tile row stride (elements)
+// LDS tiles are swizzled instead of padded.  K [key][d]: the 16-byte chunk c of row `key` sits in slot
+// c ^ (key & 7), so the 16-byte fragment reads of 32 consecutive rows fall on all banks.  V^T [d][key]:
+// key column k of row d sits at k ^ (((d >> 3) & 7) << 2): the eight rows d = 8 dc + e that one
+// transposing store instruction touches, and the rows a fragment read touches, spread over the banks,
+// while groups of four consecutive keys stay contiguous.
+constexpr int FA_KS = FA_DH;       // K tile row stride (elements)
+constexpr int FA_VS = FA_BK;       // V^T tile row stride (elements)
 
 template <typename HT>
-__global__ __launch_bounds__(256) void flash_attention_h16_kernel(const HT *__restrict__ qkv, HT *__restrict__ o,
+__global__ __launch_bounds__(256, 2) void flash_attention_h16_kernel(const HT *__restrict__ qkv, HT *__restrict__ o,
                                                                   int T, int H, float scale_log2) {
     typedef typename Half16<HT>::v8 v8;
     typedef typename Half16<HT>::v4 v4;
@@ -191,9 +196,9 @@ __global__ __launch_bounds__(256) void flash_attention_h16_kernel(const HT *__re
         for (int r = 0; r < 2; ++r) {
             const int c = tid + r * 256;
             const int key = c >> 3, dc = c & 7;
-            *reinterpret_cast<v8 *>(&Ks[key * FA_KS + dc * 8]) = kreg[r];
+            *reinterpret_cast<v8 *>(&Ks[key * FA_KS + ((dc ^ (key & 7)) << 3)]) = kreg[r];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) Vt[(dc * 8 + e) * FA_VS + key] = vreg[r][e];
+            for (int e = 0; e < 8; ++e) Vt[(dc * 8 + e) * FA_VS + (key ^ (dc << 2))] = vreg[r][e];
         }
         __syncthreads();
         if (kt + 1 < n_kt) fetch_tile(kt + 1);
@@ -207,33 +212,42 @@ __global__ __launch_bounds__(256) void flash_attention_h16_kernel(const HT *__re
             for (int v = 0; v < 16; ++v) sacc[kb][v] = 0.f;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                const v8 kf = *reinterpret_cast<const v8 *>(&Ks[(32 * kb + l32) * FA_KS + 16 * c + 8 * g]);
+                const v8 kf = *reinterpret_cast<const v8 *>(&Ks[(32 * kb + l32) * FA_KS + (((2 * c + g) ^ (l32 & 7)) << 3)]);
                 sacc[kb] = Half16<HT>::mfma(kf, qf[c], sacc[kb]);
             }
         }
-        // register v of block kb is key key0 + 32 kb + 8 (v/4) + 4 g + v%4, query qrow
+        // register v of block kb is key key0 + 32 kb + 8 (v/4) + 4 g + v%4, query qrow.  Only tiles that
+        // reach the diagonal need the causal mask (wave-uniform test); scores stay unscaled, the softmax
+        // scale (times log2 e) enters through one fused multiply-add in front of the exponential.
+        const bool diag = key0 + FA_BK - 1 > q0;
         float mx = -INFINITY;
+        if (diag) {
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+            for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int key = key0 + 32 * kb + 8 * (v >> 2) + 4 * g + (v & 3);
-                float sv = sacc[kb][v] * scale_log2;
-                sv = key <= qrow ? sv : -INFINITY;
-                sacc[kb][v] = sv;
-                mx = fmaxf(mx, sv);
-            }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+                for (int v = 0; v < 16; ++v) {
+                    const int key = key0 + 32 * kb + 8 * (v >> 2) + 4 * g + (v & 3);
+                    const float sv = key <= qrow ? sacc[kb][v] : -INFINITY;
+                    sacc[kb][v] = sv;
+                    mx = fmaxf(mx, sv);
+                }
+        } else {
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sacc[kb][v]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;     // scale > 0: the maximum commutes with it
         const float m_new = fmaxf(m_run, mx);
         // rows past the end of the sequence may see no visible key in a tile; keep them finite
         const float m_use = m_new == -INFINITY ? 0.f : m_new;
-        const float corr = exp2f(m_run - m_use);
+        const float corr = __builtin_amdgcn_exp2f(m_run - m_use);
         float psum = 0.f;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const float pv = exp2f(sacc[kb][v] - m_use);
+                const float pv = __builtin_amdgcn_exp2f(fmaf(sacc[kb][v], scale_log2, -m_use));
                 sacc[kb][v] = pv;
                 psum += pv;
             }
@@ -256,9 +270,11 @@ __global__ __launch_bounds__(256) void flash_attention_h16_kernel(const HT *__re
                 for (int e = 0; e < 8; ++e) pf[e] = from_f32<HT>(sacc[kb][8 * c2 + e]);
 #pragma unroll
                 for (int db = 0; db < 2; ++db) {
-                    const HT *vrow = &Vt[(32 * db + l32) * FA_VS + 32 * kb + 16 * c2 + 4 * g];
-                    const v4 lo = *reinterpret_cast<const v4 *>(vrow);
-                    const v4 hi = *reinterpret_cast<const v4 *>(vrow + 8);
+                    const int vsw = (((l32 >> 3) & 3) | (db << 2)) << 2;           // ((d >> 3) & 7) << 2 for d = 32 db + l32
+                    const int kcol = 32 * kb + 16 * c2 + 4 * g;
+                    const HT *vrow = &Vt[(32 * db + l32) * FA_VS];
+                    const v4 lo = *reinterpret_cast<const v4 *>(vrow + (kcol ^ vsw));
+                    const v4 hi = *reinterpret_cast<const v4 *>(vrow + ((kcol + 8) ^ vsw));
                     v8 vf;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) { vf[e] = lo[e]; vf[4 + e] = hi[e]; }
