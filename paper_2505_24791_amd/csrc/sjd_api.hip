@@ -48,6 +48,8 @@ struct BlockW {
     std::vector<LayerW> layer;
 };
 
+constexpr int SJD_ELAUNCH_RETRY = -1000;  // internal: the persistent kernel could not be launched
+
 struct ProfSpan { hipEvent_t a, b; int fam; };
 
 }  // namespace
@@ -492,7 +494,13 @@ int run_sequential_persistent(sjd_flow *f, int j, const float *z, float *x, int 
                  steps * (wbytes + kvbytes), s);
     HIP_TRY(hipMemsetAsync(f->psync, 0, 1024 * sizeof(int), s));
     hipError_t e = launch_seq_persistent(c.dtype == SJD_DTYPE_BF16, a, MB, c.width / 256, f->n_cus, f->seq_path != 3, s);
-    if (e != hipSuccess) return fail(SJD_EHIP, "persistent sequential kernel: launch failed: %s", hipGetErrorString(e));
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        // e.g. the device cannot hold one workgroup per CU right now: nothing has run yet, so in
+        // automatic mode the caller falls back to per-step launches
+        fail(SJD_EHIP, "persistent sequential kernel: launch failed: %s", hipGetErrorString(e));
+        return SJD_ELAUNCH_RETRY;
+    }
     HIP_TRY(hipMemcpyAsync(f->host_pin, f->psync + 9, sizeof(int32_t), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
     HIP_TRY(hipGetLastError());
@@ -513,8 +521,11 @@ int run_sequential(sjd_flow *f, int j, const float *z, float *x, int batch, hipS
         // attention stage (two pairs at a time per CU) and the eightfold weight traffic lose to per-step
         // launches (measured: T = 1024, W = 1024, 32 samples: 541 ms against 505 ms)
         const bool prefer_steps = f->seq_path == 0 && f->cfg.seq_len > 512 && f->cfg.width >= 1024;
-        if (f->seq_path != 1 && !prefer_steps && persistent_ok(f, batch))
-            return run_sequential_persistent(f, j, z, x, batch, s);
+        if (f->seq_path != 1 && !prefer_steps && persistent_ok(f, batch)) {
+            const int rc = run_sequential_persistent(f, j, z, x, batch, s);
+            if (rc != SJD_ELAUNCH_RETRY) return rc;
+            if (f->seq_path != 0) return SJD_EHIP;      // the persistent kernel was asked for explicitly
+        }
         if (fast_decode_ok(f)) return run_sequential_fast(f, j, z, x, batch, s);
     }
     launch_decode_epilogue(f->p, z, x, batch, T, D, -1, rev, s);  // x_1 = y_1

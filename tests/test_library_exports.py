@@ -54,3 +54,27 @@ def test_product_never_touches_the_oracle():
             if fn.endswith((".py", ".hip", ".h", ".cpp")):
                 text = open(os.path.join(dirpath, fn)).read()
                 assert "oracle" not in text.lower() or fn == "__init__.py" and "oracle" not in text.lower(), fn
+
+
+def test_bench_refuses_more_than_one_gpu_and_has_no_cpu_path():
+    """`bench.py --gpus N` with N > 1 exits with a message (this build runs on one GPU); without a
+    GPU the benchmark says so and stops instead of falling back to anything."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in r.stderr
+    import torch
+    if not torch.cuda.is_available():
+        r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py")], capture_output=True, text=True, timeout=300)
+        assert r.returncode != 0 and "no GPU" in r.stderr and not r.stdout.strip()
+
+
+def test_workloads_and_binding_agree_on_the_blob_size():
+    """The host-side size check of `sjd_flow_load_weights` uses the same layout as `workloads`:
+    a blob one float short or long is refused before any device work (checked through the formula
+    the binding exposes; the refusal itself needs a device and is a GPU test)."""
+    import workloads as wl
+    for cfg in wl.CONFIGS.values():
+        D, W, T, R, N = cfg.token_dim, cfg.width, cfg.seq_len, cfg.mlp_ratio, cfg.n_layers
+        per_layer = 2 * W + W * 3 * W + 3 * W + W * W + W + 2 * W + W * R * W + R * W + R * W * W + W
+        assert wl.block_floats(cfg) == D * W + W + T * W + N * per_layer + 2 * W + W * 2 * D + 2 * D
