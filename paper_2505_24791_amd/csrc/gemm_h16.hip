@@ -196,8 +196,8 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void gemm_h16_kernel(const HT *__r
 // wave covers 8 rows x 128 bytes - whole cache lines, which matters: at this tile size the kernel
 // moves (256+256)*2 bytes per 2*256*256 flops from L2, and half-used lines double that - and lands
 // in LDS in lane order (lane 8r + c holds a 16-byte chunk of row r).  Which chunk a lane fetches is
-// swizzled, chunk = c ^ r, so that the 16-byte fragment reads of the 32x32x16 MFMA (lane
-// l32 + 32 g wants row l32, chunk 2 ks + g) fall on all LDS banks.  The compiler does not see the
+// swizzled so that the 16-byte fragment reads of the 32x32x16 MFMA (lane l32 + 32 g wants row l32,
+// chunk 2 ks + g) fall on all LDS banks in every pass of the read (see the kernel).  The compiler does not see the
 // dependence between an LDS-direct load and a later LDS read, so the waits are written out: a
 // wave waits for its own loads of tile kt+1 before the barrier that publishes that tile.  Every
 // matrix instruction is a slot, with the LDS reads and global loads pinned between the slots.
@@ -234,15 +234,21 @@ __global__ __launch_bounds__(256, 1) void gemm_h16_dma_kernel(const HT *__restri
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     // This wave loads, per k-tile, the 8-row blocks 8 wave + i (i = 0..7) of A and of B.
-    const int lr = lane >> 3, lc = (lane & 7) ^ lr;        // row within the block, chunk fetched
+    // Row r of a 32-row fragment group keeps chunk c in slot c ^ swz(r), swz(r) = bits 1, 2 and 4 of r.
+    // A 16-byte LDS read of a wave is served in four passes of 16 lanes (lanes that agree in bits 3 and
+    // 5), 64 banks wide: the 16 rows of a pass ({0-7, 16-23} or {8-15, 24-31} of the group, one chunk)
+    // must fall on 16 different 16-byte bank groups, (8 (r & 1) + slot) mod 16 - which this does.
+    const int lr = lane >> 3;                              // row within the 8-row block
+    const int lc0 = (lane & 7) ^ ((lr >> 1) & 3);          // chunk fetched, blocks with bit 4 of the row clear
     uint32_t a_eoff[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         int row = m0 + (wave * 8 + i) * 8 + lr;
         row = row < M ? row : M - 1;                       // rows past the end: re-read the last row, never stored
-        a_eoff[i] = (uint32_t)row * (uint32_t)K + (uint32_t)(lc * 8);
+        a_eoff[i] = (uint32_t)row * (uint32_t)K + (uint32_t)((lc0 ^ (((i >> 1) & 1) << 2)) * 8);
     }
-    const uint32_t b_eoff = (uint32_t)(n0 + wave * 64 + lr) * (uint32_t)K + (uint32_t)(lc * 8);
+    const uint32_t b_row = (uint32_t)(n0 + wave * 64 + lr) * (uint32_t)K;
+    const uint32_t b_eoff[2] = {b_row + (uint32_t)(lc0 * 8), b_row + (uint32_t)((lc0 ^ 4) * 8)};
     const size_t b_istep = (size_t)8 * K;                   // Bt rows are padded to the tile: no clamp
     const int KT = K / BK;
     auto issue_load = [&](int kt_, int q) {                 // block q (0..15) of this wave's sixteen
@@ -253,18 +259,18 @@ __global__ __launch_bounds__(256, 1) void gemm_h16_dma_kernel(const HT *__restri
                                              16, 0, 0);
         } else {
             const int i = q - 8;
-            __builtin_amdgcn_global_load_lds(SJD_GPTR(Bt + (size_t)ktc * BK + i * b_istep + b_eoff),
+            __builtin_amdgcn_global_load_lds(SJD_GPTR(Bt + (size_t)ktc * BK + i * b_istep + b_eoff[(i >> 1) & 1]),
                                              SJD_LPTR(st + OPB + (wave * 8 + i) * 1024), 16, 0, 0);
         }
     };
     v8 fa[2][MI], fb[2][NI];
     // fragment (32 rows of row block r of the wave's sub-tile, k-step ks): row l32 is row l32 & 7 of
-    // 8-row block 4 r + (l32 >> 3); its chunk 2 ks + g sits in slot (2 ks + g) ^ (l32 & 7)
-    const int rr = l32 & 7;
-    const int frag_base = (l32 >> 3) * 1024 + rr * 128;
+    // 8-row block 4 r + (l32 >> 3); its chunk 2 ks + g sits in slot (2 ks + g) ^ swz(l32)
+    const int swz = ((l32 >> 1) & 3) | (((l32 >> 4) & 1) << 2);
+    const int frag_base = l32 * 128;
     int frag_k[KSUB];
 #pragma unroll
-    for (int ks = 0; ks < KSUB; ++ks) frag_k[ks] = frag_base + (((2 * ks + g) ^ rr) << 4);
+    for (int ks = 0; ks < KSUB; ++ks) frag_k[ks] = frag_base + (((2 * ks + g) ^ swz) << 4);
     auto read_one = [&](int stage, int ks, int buf, int r) {
         const unsigned char *st = smem_raw + stage * STB + frag_k[ks];
         if (r < MI) fa[buf][r] = *reinterpret_cast<const v8 *>(st + (wm * 16 + 4 * r) * 1024);
