@@ -25,7 +25,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # Bytes per launch that the L2s requested from / wrote to the memory side, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs of `bench.py --counters`, scaled by what the same counters read for a 256 MiB copy
 # (profiles/bench_c2_hbm_counters.md).  Keyed by (workload, kernel family); anything else reports null.
-MEASURED_TRAFFIC_BYTES = {("C2", "decode_fused"): 7.11e10, ("C2", "decode_gemm"): 2.97e6}
+MEASURED_TRAFFIC_BYTES = {("C2", "decode_fused"): 7.13e10, ("C2", "decode_gemm"): 2.97e6}
 
 
 def parse():

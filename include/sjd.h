@@ -65,7 +65,7 @@ typedef struct sjd_flow sjd_flow; /* opaque */
 typedef struct {
     int32_t n_blocks;   /* K, 1..SJD_MAX_BLOCKS */
     int32_t n_layers;   /* N >= 1 */
-    int32_t width;      /* W, a multiple of n_heads; the 16-bit modes need W % 64 == 0 */
+    int32_t width;      /* W, a multiple of n_heads and of 4; the 16-bit modes need W % 64 == 0 */
     int32_t n_heads;    /* H */
     int32_t mlp_ratio;  /* hidden = mlp_ratio * W */
     int32_t seq_len;    /* T >= 1 */

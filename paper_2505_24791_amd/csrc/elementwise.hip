@@ -7,8 +7,9 @@ namespace sjd {
 
 // ------------------------------------------------------------------------------------------------
 // Embedding: h[m, :] = x[b, tok, :] * w_in + b_in + pos[p, :]   (p = processing position of row m)
-// A workgroup handles EMB_ROWS rows: a thread keeps its columns of w_in in registers across the
-// rows (D is small, tens; W up to a few thousand), so w_in is read from L2 once per EMB_ROWS rows.
+// A workgroup handles EMB_ROWS rows; a work item is four adjacent columns of eight of them: the
+// four columns of w_in stay in registers across the rows (D is small, tens; W up to a few thousand),
+// so w_in is read from L2 once per EMB_ROWS rows, and h is written 16 bytes per lane.  W % 4 == 0.
 constexpr int EMB_ROWS = 16;
 __global__ __launch_bounds__(256) void embed_kernel(const float *__restrict__ x, const float *__restrict__ w_in,
                                                     const float *__restrict__ b_in, const float *__restrict__ pos,
@@ -17,30 +18,46 @@ __global__ __launch_bounds__(256) void embed_kernel(const float *__restrict__ x,
     __shared__ int prow[EMB_ROWS];
     const int m0 = blockIdx.x * EMB_ROWS;
     const int rows = n_rows - m0 < EMB_ROWS ? n_rows - m0 : EMB_ROWS;
-    for (int e = threadIdx.x; e < rows * D; e += 256) {
+    for (int e = threadIdx.x; e < EMB_ROWS * D; e += 256) {
         const int r = e / D, d = e - r * D;
-        const int m = m0 + r;
-        const int i = m / map.rows_per_sample;
-        const int p = map.t0 + m % map.rows_per_sample;
-        const int b = map.active ? map.active[i] : i;
-        const int tok = map.reversed ? map.T - 1 - p : p;
-        xs[e] = x[((size_t)b * map.T + tok) * D + d];
-        if (d == 0) prow[r] = p;
+        float v = 0.f;
+        if (r < rows) {
+            const int m = m0 + r;
+            const int i = m / map.rows_per_sample;
+            const int p = map.t0 + m % map.rows_per_sample;
+            const int b = map.active ? map.active[i] : i;
+            const int tok = map.reversed ? map.T - 1 - p : p;
+            v = x[((size_t)b * map.T + tok) * D + d];
+            if (d == 0) prow[r] = p;
+        }
+        xs[e] = v;
     }
     __syncthreads();
-    for (int w = threadIdx.x; w < W; w += 256) {
-        float acc[EMB_ROWS];
-        const float bias = b_in[w];
+    const int ncg = W >> 2;
+    for (int it = threadIdx.x; it < 2 * ncg; it += 256) {
+        const int rh = it / ncg, w = (it - rh * ncg) * 4, r0 = rh * (EMB_ROWS / 2);
+        const f32x4 bias = *reinterpret_cast<const f32x4 *>(b_in + w);
+        f32x4 acc[EMB_ROWS / 2];
 #pragma unroll
-        for (int r = 0; r < EMB_ROWS; ++r) acc[r] = bias;
+        for (int r = 0; r < EMB_ROWS / 2; ++r) acc[r] = bias;
         for (int d = 0; d < D; ++d) {
-            const float wv = w_in[(size_t)d * W + w];
+            const f32x4 wv = *reinterpret_cast<const f32x4 *>(w_in + (size_t)d * W + w);
 #pragma unroll
-            for (int r = 0; r < EMB_ROWS; ++r) acc[r] = fmaf(r < rows ? xs[r * D + d] : 0.f, wv, acc[r]);
+            for (int r = 0; r < EMB_ROWS / 2; ++r) {
+                const float xv = xs[(r0 + r) * D + d];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[r][e] = fmaf(xv, wv[e], acc[r][e]);
+            }
         }
 #pragma unroll
-        for (int r = 0; r < EMB_ROWS; ++r)
-            if (r < rows) h[(size_t)(m0 + r) * W + w] = acc[r] + pos[(size_t)prow[r] * W + w];
+        for (int r = 0; r < EMB_ROWS / 2; ++r)
+            if (r0 + r < rows) {
+                const f32x4 pv = *reinterpret_cast<const f32x4 *>(pos + (size_t)prow[r0 + r] * W + w);
+                f32x4 o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] = acc[r][e] + pv[e];
+                *reinterpret_cast<f32x4 *>(h + (size_t)(m0 + r0 + r) * W + w) = o;
+            }
     }
 }
 

@@ -550,6 +550,7 @@ int sjd_flow_create(const sjd_config *cfg, sjd_flow **out) {
         c.max_batch < 1)
         return fail(SJD_EINVAL, "all sizes must be positive");
     if (c.width % c.n_heads) return fail(SJD_EINVAL, "width %d is not a multiple of n_heads %d", c.width, c.n_heads);
+    if (c.width % 4) return fail(SJD_EINVAL, "width %d is not a multiple of 4", c.width);
     if (c.dtype != SJD_DTYPE_F32 && c.dtype != SJD_DTYPE_BF16 && c.dtype != SJD_DTYPE_F16)
         return fail(SJD_EINVAL, "unknown dtype %d", c.dtype);
     if (c.dtype != SJD_DTYPE_F32 && c.width % 64) return fail(SJD_EINVAL, "16-bit modes need width %% 64 == 0");
