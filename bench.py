@@ -49,6 +49,10 @@ def parse():
                     help="schedule of sequential blocks: 0 automatic, 1 per-step launches replayed as a graph, 2 "
                          "persistent kernel (cooperative launch), 3 persistent kernel with an ordinary launch (for "
                          "runs under rocprofv3, which does not survive cooperative launches here)")
+    ap.add_argument("--pipeline-cus", type=int, default=128,
+                    help="also time the steps with two batches in flight: the sequential block of one batch on this "
+                         "many CUs (a multiple of 32) beside the Jacobi blocks of the previous batch on the rest; "
+                         "reported as an extra object, `value` stays the one-batch-at-a-time figure; 0 = skip")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-seq", action="store_true", help="skip the GPU all-sequential baseline")
     ap.add_argument("--cpu-samples", type=int, default=0, help="samples for the CPU baseline (0 = one per thread)")
@@ -135,6 +139,7 @@ def main() -> int:
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
     value = cfg.batch * args.steps / dt
+    x_sel = x.clone()
 
     # ---- the same steps again with events around every launch of every kernel family
     flow.profile_enable(range(sjd.PROF_FAMILIES))
@@ -182,6 +187,27 @@ def main() -> int:
         torch.cuda.synchronize()
         seq_ms = (time.perf_counter() - t0) / n_seq * 1e3
 
+    # ---- the same steps with two batches in flight (see paper_2505_24791_amd/pipeline.py)
+    piped = None
+    if args.pipeline_cus and args.mode == "selective" and cfg.bf16 and K > 1:
+        try:
+            from paper_2505_24791_amd.pipeline import PipelinedSampler
+            ps = PipelinedSampler(cfg, blob, n_seq_cus=args.pipeline_cus)
+            outs, _ = ps.run([z] * max(2, args.warmup), opts)
+            same = bool(torch.equal(outs[-1], x_sel))
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            ps.run([z] * args.steps, opts)
+            torch.cuda.synchronize()
+            pdt = time.perf_counter() - t0
+            ps.close()
+            piped = {"value": cfg.batch * args.steps / pdt, "unit": "samples/s", "ms_per_step": pdt / args.steps * 1e3,
+                     "steps": args.steps, "batches_in_flight": 2, "sequential_cus": args.pipeline_cus,
+                     "outputs_equal_one_at_a_time": same,
+                     "note": "block 0 of batch i+1 on a CU-masked stream beside blocks 1.. of batch i; includes fill and drain"}
+        except Exception as e:   # noqa: BLE001 - an optional extra measurement must not take the line away
+            piped = {"error": f"{type(e).__name__}: {e}"}
+
     # ---- CPU oracle on a bounded sample: one sample per host thread, the full cascade
     cpu = None
     if not args.no_cpu:
@@ -223,6 +249,7 @@ def main() -> int:
         "speedup_vs_gpu_sequential": (seq_ms / ms_per_step) if seq_ms else None,
         "paper_context": "up to 4.7x over sequential on 2x NVIDIA L40S with trained weights (Table 1); not comparable",
         "device_bytes": flow.device_bytes,
+        "two_batches_in_flight": piped,
         "roofline": roof,
         "cpu_baseline": cpu,
     }

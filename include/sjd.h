@@ -210,6 +210,15 @@ SJD_API int sjd_flow_set_mask_nearest(sjd_flow *flow, int o);
  * key/value cache of Sec. 3.5; they differ in how the T-1 dependent steps are scheduled on the GPU. */
 SJD_API int sjd_flow_set_sequential_path(sjd_flow *flow, int path);
 
+/* Number of workgroups of the persistent sequential kernel: 0 (the default) = one per CU of the device,
+ * else a multiple of 32 in 32..CUs (SJD_EINVAL otherwise).  For callers that run the sequential block of
+ * one batch beside other work, on a stream restricted to that many CUs by a CU mask: the kernel needs
+ * all its workgroups resident at once, one per CU, and finds its XCD groups by itself.  The mask must
+ * enable the same number of CUs in every shader engine of every XCD (on this part: mask bits
+ * 0 .. n_cus-1), or a workgroup may never be placed and the call ends with SJD_EHIP after its bounded
+ * wait.  Use path 3 (ordinary launch) there.  Results do not depend on the count. */
+SJD_API int sjd_flow_set_sequential_cus(sjd_flow *flow, int n_cus);
+
 /* Kernel-family timing: when enabled, every launch of the selected families (bit f of
  * family_mask = SJD_PROF_* f) is bracketed by events on the caller's stream.  Costs a little time per launch. */
 SJD_API int sjd_profile_enable(sjd_flow *flow, uint32_t family_mask);

@@ -25,7 +25,7 @@ PROF_NAMES = ("gemm", "attention", "epilogue", "decode_gemm", "decode_attn", "ot
 
 EXPORTS = ("sjd_flow_create", "sjd_flow_load_weights", "sjd_jacobi_inverse_block", "sjd_sequential_inverse_block",
            "sjd_sample", "sjd_conditioner", "sjd_op_linear_h16", "sjd_jacobi_trace_block", "sjd_forward_block",
-           "sjd_forward", "sjd_flow_set_mask_nearest", "sjd_flow_set_sequential_path", "sjd_profile_enable", "sjd_profile_read", "sjd_flow_device_bytes",
+           "sjd_forward", "sjd_flow_set_mask_nearest", "sjd_flow_set_sequential_path", "sjd_flow_set_sequential_cus", "sjd_profile_enable", "sjd_profile_read", "sjd_flow_device_bytes",
            "sjd_last_error", "sjd_flow_destroy")
 
 
@@ -80,6 +80,7 @@ def load_library() -> C.CDLL:
     lib.sjd_forward_block.argtypes = [vp, C.c_int, vp, vp, vp, C.c_int, C.c_int, vp]
     lib.sjd_forward.argtypes = [vp, vp, vp, vp, C.c_int, vp]
     lib.sjd_flow_set_sequential_path.argtypes = [vp, C.c_int]
+    lib.sjd_flow_set_sequential_cus.argtypes = [vp, C.c_int]
     lib.sjd_flow_set_mask_nearest.argtypes = [vp, C.c_int]
     lib.sjd_op_linear_h16.argtypes = [C.c_int, C.c_int, vp, vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, vp]
     lib.sjd_profile_enable.argtypes = [vp, C.c_uint32]
@@ -279,6 +280,10 @@ class Flow:
     def set_sequential_path(self, path: int) -> None:
         """0 automatic, 1 per-step launches (graph replay), 2 persistent kernel, 3 the same with a plain launch."""
         _check(self.lib.sjd_flow_set_sequential_path(self._h, path))
+
+    def set_sequential_cus(self, n_cus: int) -> None:
+        """Workgroups of the persistent sequential kernel: 0 = one per CU of the device, else a multiple of 32."""
+        _check(self.lib.sjd_flow_set_sequential_cus(self._h, n_cus))
 
     def profile_enable(self, families) -> None:
         mask = 0

@@ -8,6 +8,7 @@
 // No split-K and no atomics: an output row depends only on its own row of A, so results are
 // independent of which other rows share the tile or the batch.
 #include "common.h"
+#include <atomic>
 
 namespace sjd {
 
@@ -323,10 +324,10 @@ static void launch_dma(const HT *A, const HT *Bt, const float *bias, const float
     const int grid = ((n_tiles + 7) / 8) * 8;
     const size_t smem = 4 * 32 * 1024;
     auto kern = gemm_h16_dma_kernel<HT, OutT, EPI>;
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::atomic<bool> attr_set{false};   // callers may come from several host threads
+    if (!attr_set.load(std::memory_order_acquire)) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), smem, s, A, Bt, bias, resid, C, M, N, K, tiles_n, n_tiles);
 }
@@ -341,10 +342,10 @@ static void launch_tile(const HT *A, const HT *Bt, const float *bias, const floa
     const size_t ep = (size_t)4 * 32 * (BN / 2 + 4) * sizeof(float);  // epilogue parking space
     if (smem < ep) smem = ep;
     auto kern = gemm_h16_kernel<HT, BM, BN, BK, WGS_PER_CU, OutT, EPI>;
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::atomic<bool> attr_set{false};   // callers may come from several host threads
+    if (!attr_set.load(std::memory_order_acquire)) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), smem, s, A, Bt, bias, resid, C, M, N, K, tiles_n, n_tiles);
 }

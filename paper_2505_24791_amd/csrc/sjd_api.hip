@@ -82,7 +82,7 @@ struct sjd_flow {
     int mask_nearest = 0;        // o of the masked-dependency probe (eq. 6); 0: plain causal attention
     int seq_path = 0;            // 0 automatic, 1 per-step launches (graph replay), 2 persistent kernel, 3 the same, plain launch
     int *psync = nullptr;        // synchronisation words of the persistent kernel (1024 ints)
-    int n_cus = 0, coop = 0;
+    int n_cus = 0, n_cus_device = 0, coop = 0;   // workgroups of the persistent kernel; CUs of the device
     hipEvent_t ev[SJD_MAX_BLOCKS + 1] = {};
     // profiling
     uint32_t prof_mask = 0;
@@ -600,7 +600,7 @@ int sjd_flow_create(const sjd_config *cfg, sjd_flow **out) {
     {
         hipDeviceProp_t prop;
         if (rc == SJD_OK && hipGetDeviceProperties(&prop, f->device) == hipSuccess) {
-            f->n_cus = prop.multiProcessorCount;
+            f->n_cus = f->n_cus_device = prop.multiProcessorCount;
             f->coop = prop.cooperativeLaunch;
         }
     }
@@ -901,6 +901,15 @@ int sjd_flow_set_sequential_path(sjd_flow *f, int path) {
     if (path < 0 || path > 3)
         return fail(SJD_EINVAL, "path must be 0 (automatic), 1 (per-step launches), 2 (persistent kernel) or 3 (the same, plain launch)");
     f->seq_path = path;
+    return SJD_OK;
+}
+
+int sjd_flow_set_sequential_cus(sjd_flow *f, int n_cus) {
+    if (!f) return fail(SJD_EINVAL, "null flow");
+    if (n_cus != 0 && (n_cus < 32 || n_cus > f->n_cus_device || n_cus % 32))
+        return fail(SJD_EINVAL, "the persistent kernel's workgroup count must be 0 (one per CU of the device) or a multiple of 32 in 32..%d",
+                    f->n_cus_device);
+    f->n_cus = n_cus ? n_cus : f->n_cus_device;
     return SJD_OK;
 }
 

@@ -78,3 +78,13 @@ def test_workloads_and_binding_agree_on_the_blob_size():
         D, W, T, R, N = cfg.token_dim, cfg.width, cfg.seq_len, cfg.mlp_ratio, cfg.n_layers
         per_layer = 2 * W + W * 3 * W + 3 * W + W * W + W + 2 * W + W * R * W + R * W + R * W * W + W
         assert wl.block_floats(cfg) == D * W + W + T * W + N * per_layer + 2 * W + W * 2 * D + 2 * D
+
+
+def test_cu_mask_ranges_are_validated_before_any_device_call():
+    # host logic of the pipelined sampler: ranges that would leave a shader engine with fewer CUs than
+    # another are refused before the HIP runtime is touched
+    import pytest
+    from paper_2505_24791_amd.pipeline import masked_stream
+    for first, last in ((0, 48), (8, 64), (64, 64), (128, 96), (0, 288), (-32, 64)):
+        with pytest.raises(ValueError):
+            masked_stream(first, last)
