@@ -13,6 +13,7 @@ Argument marshalling and stream plumbing only: every step runs in the library's 
 import ctypes as C
 import queue
 import threading
+import time
 from typing import List, Optional
 
 from . import Flow, JacobiOpts, DTYPE_F16
@@ -59,6 +60,7 @@ class PipelinedSampler:
         self.cfg = cfg
         self.n_seq_cus = n_seq_cus
         self.flows: List[Flow] = []
+        self.last_timing = None
         for _ in range(2):
             f = Flow(cfg, dtype=dtype)
             f.load_weights(weights_blob)
@@ -90,13 +92,16 @@ class PipelinedSampler:
         handover: "queue.Queue" = queue.Queue()
         free = [threading.Semaphore(1), threading.Semaphore(1)]   # a flow's workspace: one batch at a time
         errors = []
+        seq_ms, jac_ms = [], []          # host-side duration of every sequential block / Jacobi cascade
 
         def seq_worker():
             try:
                 with torch.cuda.stream(self.seq_stream):
                     for i in range(n):
                         free[i & 1].acquire()
+                        t0 = time.perf_counter()
                         x0 = self.flows[i & 1].sequential_inverse_block(0, latents[i])   # returns when the block is done
+                        seq_ms.append((time.perf_counter() - t0) * 1e3)
                         handover.put((i, x0))
             except BaseException as e:   # noqa: BLE001 - reported to the caller below
                 errors.append(e)
@@ -111,11 +116,13 @@ class PipelinedSampler:
                         if item is None:
                             break
                         i, x = item
+                        t0 = time.perf_counter()
                         counts = [self.cfg.seq_len - 1]
                         for j in range(1, K):
                             x, _, launched, _ = self.flows[i & 1].jacobi_inverse_block(j, x, opts)
                             counts.append(launched)
                         outs[i], passes[i] = x, counts
+                        jac_ms.append((time.perf_counter() - t0) * 1e3)
                         free[i & 1].release()
             except BaseException as e:   # noqa: BLE001
                 errors.append(e)
@@ -130,4 +137,5 @@ class PipelinedSampler:
         if errors:
             raise errors[0]
         torch.cuda.synchronize()
+        self.last_timing = {"sequential_ms": seq_ms, "jacobi_ms": jac_ms}
         return outs, passes
