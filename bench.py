@@ -49,10 +49,12 @@ def parse():
                     help="schedule of sequential blocks: 0 automatic, 1 per-step launches replayed as a graph, 2 "
                          "persistent kernel (cooperative launch), 3 persistent kernel with an ordinary launch (for "
                          "runs under rocprofv3, which does not survive cooperative launches here)")
-    ap.add_argument("--pipeline-cus", type=int, default=128,
+    ap.add_argument("--pipeline-cus", type=int, default=-1,
                     help="also time the steps with two batches in flight: the sequential block of one batch on this "
                          "many CUs (a multiple of 32) beside the Jacobi blocks of the previous batch on the rest; "
-                         "reported as an extra object, `value` stays the one-batch-at-a-time figure; 0 = skip")
+                         "reported as an extra object, `value` stays the one-batch-at-a-time figure; 0 = skip, "
+                         "-1 = 128 if the sequential block takes at least 40 %% of a step (else skip: with little "
+                         "sequential work there is nothing to hide)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-seq", action="store_true", help="skip the GPU all-sequential baseline")
     ap.add_argument("--cpu-samples", type=int, default=0, help="samples for the CPU baseline (0 = one per thread)")
@@ -189,10 +191,13 @@ def main() -> int:
 
     # ---- the same steps with two batches in flight (see paper_2505_24791_amd/pipeline.py)
     piped = None
-    if args.pipeline_cus and args.mode == "selective" and cfg.bf16 and K > 1:
+    pipe_cus = args.pipeline_cus
+    if pipe_cus < 0:
+        pipe_cus = 128 if stats["block_ms"][0] >= 0.4 * sum(stats["block_ms"][:K]) else 0
+    if pipe_cus and args.mode == "selective" and cfg.bf16 and K > 1:
         try:
             from paper_2505_24791_amd.pipeline import PipelinedSampler
-            ps = PipelinedSampler(cfg, blob, n_seq_cus=args.pipeline_cus)
+            ps = PipelinedSampler(cfg, blob, n_seq_cus=pipe_cus)
             outs, _ = ps.run([z] * max(2, args.warmup), opts)
             same = bool(torch.equal(outs[-1], x_sel))
             torch.cuda.synchronize()
@@ -202,7 +207,7 @@ def main() -> int:
             pdt = time.perf_counter() - t0
             ps.close()
             piped = {"value": cfg.batch * args.steps / pdt, "unit": "samples/s", "ms_per_step": pdt / args.steps * 1e3,
-                     "steps": args.steps, "batches_in_flight": 2, "sequential_cus": args.pipeline_cus,
+                     "steps": args.steps, "batches_in_flight": 2, "sequential_cus": pipe_cus,
                      "outputs_equal_one_at_a_time": same,
                      "note": "block 0 of batch i+1 on a CU-masked stream beside blocks 1.. of batch i; includes fill and drain"}
         except Exception as e:   # noqa: BLE001 - an optional extra measurement must not take the line away
