@@ -45,6 +45,8 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[MI][NI], unsigned ch
     f32x4 bv4 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int e = 0; e < 4; ++e) bv4[e] = (colg + e < N) ? bias[colg + e] : 0.f;
+    constexpr int NQ = 32 / RPI;               // read-back instructions per 32 rows
+    const bool vec_ok = colg + 3 < N && (N & 3) == 0;
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
         __builtin_amdgcn_wave_barrier();
@@ -52,35 +54,57 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[MI][NI], unsigned ch
         for (int j = 0; j < NI; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) ep[(8 * (v >> 2) + 4 * g + (v & 3)) * EP + 32 * j + l32] = acc[i][j][v];
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        // a wave's LDS operations complete in order: the reads below see these writes without a wait;
+        // the compiler only has to keep the order
+        asm volatile("" ::: "memory");
         __builtin_amdgcn_wave_barrier();
+        // All reads (LDS, then the residual) are issued before the first store: a wait for a load while
+        // stores are in flight waits for the stores as well (one counter, no order between the two kinds),
+        // which, once per row group, used to be most of the epilogue's time.
+        f32x4 val[NQ], res[NQ];
 #pragma unroll
-        for (int rr = 0; rr < 32; rr += RPI) {
-            const int rloc = rr + rl;
-            const int row = row0 + 32 * i + rloc;
-            f32x4 val = *reinterpret_cast<const f32x4 *>(&ep[rloc * EP + cl]);
+        for (int q = 0; q < NQ; ++q) val[q] = *reinterpret_cast<const f32x4 *>(&ep[(q * RPI + rl) * EP + cl]);
+        if (EPI == EPI_BIAS_RESIDUAL && sizeof(OutT) == 4 && vec_ok) {
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) {
+                const int row = row0 + 32 * i + q * RPI + rl;
+                const int rc = row < M ? row : M - 1;        // rows past the end: any valid row, value not used
+                res[q] = *reinterpret_cast<const f32x4 *>(resid + (size_t)rc * N + colg);
+            }
+        }
+        // Uses in straight-line code: the waits for the loads above are placed here, once.  Left to the
+        // conditional blocks below, every block waits again "for the bias" (it cannot know that an
+        // earlier, skipped block already did) and with that for the stores issued so far.
+        asm volatile("" : "+v"(bv4));
+        if (EPI == EPI_BIAS_RESIDUAL && sizeof(OutT) == 4 && vec_ok) {
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) asm volatile("" : "+v"(res[q]));
+        }
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+            const int row = row0 + 32 * i + q * RPI + rl;
             if (row < M && colg < N) {
-                val += bv4;
+                f32x4 v4 = val[q] + bv4;
                 if (EPI == EPI_BIAS_GELU) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) val[e] = gelu_erf_h16(val[e]);
+                    for (int e = 0; e < 4; ++e) v4[e] = gelu_erf_h16(v4[e]);
                 }
                 OutT *dst = C + (size_t)row * N + colg;
-                if (colg + 3 < N && (N & 3) == 0) {
+                if (vec_ok) {
                     if constexpr (sizeof(OutT) == 4) {
-                        if (EPI == EPI_BIAS_RESIDUAL) val += *reinterpret_cast<const f32x4 *>(resid + (size_t)row * N + colg);
-                        *reinterpret_cast<f32x4 *>(dst) = val;
+                        if (EPI == EPI_BIAS_RESIDUAL) v4 += res[q];
+                        *reinterpret_cast<f32x4 *>(dst) = v4;
                     } else {
                         typename Half16<HT>::v4 o4;
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) o4[e] = from_f32<HT>(val[e]);
+                        for (int e = 0; e < 4; ++e) o4[e] = from_f32<HT>(v4[e]);
                         *reinterpret_cast<typename Half16<HT>::v4 *>(dst) = o4;
                     }
                 } else {  // ragged right edge, or rows not 16-byte aligned
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
                         if (colg + e < N) {
-                            float t = val[e];
+                            float t = v4[e];
                             if (EPI == EPI_BIAS_RESIDUAL) t += resid[(size_t)row * N + colg + e];
                             dst[e] = from_f32<OutT>(t);
                         }
@@ -122,8 +146,11 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void gemm_h16_kernel(const HT *__r
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // global -> register staging: chunk c covers row c/CPR, k offset 8*(c%CPR)
-    v8 ra[A_CHUNKS], rb[B_CHUNKS];
+    // global -> register staging: chunk c covers row c/CPR, k offset 8*(c%CPR).  Two register sets, so
+    // that two k-tiles can be on their way while a third is multiplied: at K = 512 a k-tile is 0.25 us
+    // of matrix work against 1 us of load latency.
+    struct Regs { v8 a[A_CHUNKS], b[B_CHUNKS]; };
+    Regs S0, S1;
     const HT *a_ptr[A_CHUNKS];
     const HT *b_ptr[B_CHUNKS];
 #pragma unroll
@@ -138,39 +165,28 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void gemm_h16_kernel(const HT *__r
         const int c = tid + r * 256;
         b_ptr[r] = Bt + (size_t)(n0 + c / CPR) * K + (c % CPR) * 8;  // Bt rows are padded up to the tile
     }
-    auto load_tile = [&](int kt) {
+    auto load_tile = [&](int kt, Regs &q) {
 #pragma unroll
-        for (int r = 0; r < A_CHUNKS; ++r) ra[r] = *reinterpret_cast<const v8 *>(a_ptr[r] + (size_t)kt * G_BK);
+        for (int r = 0; r < A_CHUNKS; ++r) q.a[r] = *reinterpret_cast<const v8 *>(a_ptr[r] + (size_t)kt * G_BK);
 #pragma unroll
-        for (int r = 0; r < B_CHUNKS; ++r) rb[r] = *reinterpret_cast<const v8 *>(b_ptr[r] + (size_t)kt * G_BK);
+        for (int r = 0; r < B_CHUNKS; ++r) q.b[r] = *reinterpret_cast<const v8 *>(b_ptr[r] + (size_t)kt * G_BK);
     };
-    auto store_tile = [&](int stage) {
+    auto store_tile = [&](int stage, const Regs &q) {
         HT *As = smem + stage * STAGE, *Bs = As + BM * G_LDS_STRIDE;
 #pragma unroll
         for (int r = 0; r < A_CHUNKS; ++r) {
             const int c = tid + r * 256;
-            *reinterpret_cast<v8 *>(&As[(c / CPR) * G_LDS_STRIDE + (c % CPR) * 8]) = ra[r];
+            *reinterpret_cast<v8 *>(&As[(c / CPR) * G_LDS_STRIDE + (c % CPR) * 8]) = q.a[r];
         }
 #pragma unroll
         for (int r = 0; r < B_CHUNKS; ++r) {
             const int c = tid + r * 256;
-            *reinterpret_cast<v8 *>(&Bs[(c / CPR) * G_LDS_STRIDE + (c % CPR) * 8]) = rb[r];
+            *reinterpret_cast<v8 *>(&Bs[(c / CPR) * G_LDS_STRIDE + (c % CPR) * 8]) = q.b[r];
         }
     };
-
-    // two LDS stages: while stage kt&1 is multiplied, tile kt+1 is written to the other stage and
-    // tile kt+2 is on its way from global memory
-    const int KT = K / G_BK;
-    load_tile(0);
-    store_tile(0);
-    if (KT > 1) load_tile(1);
-    __syncthreads();
     constexpr int KSUB = G_BK / 16;
-    for (int kt = 0; kt < KT; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < KT) store_tile(cur ^ 1);
-        if (kt + 2 < KT) load_tile(kt + 2);
-        const HT *As = smem + cur * STAGE, *Bs = As + BM * G_LDS_STRIDE;
+    auto multiply = [&](int stage) {
+        const HT *As = smem + stage * STAGE, *Bs = As + BM * G_LDS_STRIDE;
 #pragma unroll
         for (int ks = 0; ks < KSUB; ++ks) {
             v8 fa[MI], fb[NI];
@@ -185,7 +201,47 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void gemm_h16_kernel(const HT *__r
 #pragma unroll
                 for (int j = 0; j < NI; ++j) acc[i][j] = Half16<HT>::mfma(fa[i], fb[j], acc[i][j]);
         }
+    };
+
+    const int KT = K / G_BK;
+    if (KT >= 4 && (KT & 1) == 0) {
+        // Two LDS stages and two register sets; tile t travels in set t & 1.  In iteration kt, tile kt+1
+        // goes from its set to stage (kt+1)&1, the set is refilled with tile kt+3, stage kt&1 is
+        // multiplied.  The steady state and the last three iterations are written out without
+        // conditions: a wait for the older set's loads then leaves the newer set's in flight (with
+        // conditions around the loads the compiler has to wait for everything at every join).
+        load_tile(0, S0);
+        __builtin_amdgcn_sched_barrier(0);   // keep the issue order of the sets: the waits count loads
+        load_tile(1, S1);
+        __builtin_amdgcn_sched_barrier(0);
+        store_tile(0, S0);
+        load_tile(2, S0);
+        __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
+        int kt = 0;
+        for (; kt + 5 < KT; kt += 2) {
+            store_tile(1, S1); load_tile(kt + 3, S1); multiply(0); __syncthreads();
+            store_tile(0, S0); load_tile(kt + 4, S0); multiply(1); __syncthreads();
+        }
+        // kt == KT - 4 (even)
+        store_tile(1, S1); load_tile(kt + 3, S1); multiply(0); __syncthreads();
+        store_tile(0, S0); multiply(1); __syncthreads();
+        store_tile(1, S1); multiply(0); __syncthreads();
+        multiply(1);
+        __syncthreads();
+    } else {
+        // any other k-tile count: one register set, conditions in the loop
+        load_tile(0, S0);
+        store_tile(0, S0);
+        if (KT > 1) load_tile(1, S0);
+        __syncthreads();
+        for (int kt = 0; kt < KT; ++kt) {
+            const int cur = kt & 1;
+            if (kt + 1 < KT) store_tile(cur ^ 1, S0);
+            if (kt + 2 < KT) load_tile(kt + 2, S0);
+            multiply(cur);
+            __syncthreads();
+        }
     }
 
     tile_epilogue<HT, MI, NI, BN, OutT, EPI>(acc, smem_raw, bias, resid, C, M, N, m0 + wm0, n0 + wn0, lane, wave);
