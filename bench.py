@@ -193,7 +193,9 @@ def main() -> int:
     piped = None
     pipe_cus = args.pipeline_cus
     if pipe_cus < 0:
-        pipe_cus = 128 if stats["block_ms"][0] >= 0.4 * sum(stats["block_ms"][:K]) else 0
+        # automatic: only where block 0 is a large share of a step and runs as the persistent kernel anyway
+        persistent_default = not (cfg.seq_len > 512 and cfg.width >= 1024)
+        pipe_cus = 128 if persistent_default and stats["block_ms"][0] >= 0.4 * sum(stats["block_ms"][:K]) else 0
     if pipe_cus and args.mode == "selective" and cfg.bf16 and K > 1:
         try:
             from paper_2505_24791_amd.pipeline import PipelinedSampler
