@@ -9,7 +9,9 @@ import pytest
 pytestmark = pytest.mark.gpu
 
 KERNELS = {1: "256x128x32 staged", 2: "256x256x64 LDS-direct", 3: "128x128x64", 0: "auto"}
-SHAPES = [(300, 200, 128), (700, 1000, 64), (513, 257, 320), (1024, 768, 256)]
+# K values give the register-staged kernels 1..16 k-tiles: both main loops (two register sets from 4
+# k-tiles on when the count is even, else one set) with zero, one and several steady-state iterations
+SHAPES = [(300, 200, 128), (700, 1000, 64), (513, 257, 320), (1024, 768, 256), (400, 384, 512), (260, 130, 384)]
 
 
 @pytest.fixture(scope="module")
