@@ -82,14 +82,17 @@ __device__ __forceinline__ float gelu_erf(float v) { return 0.5f * v * (1.0f + e
 // formula 7.1.26 of Abramowitz & Stegun (absolute error below 1.5e-7, far inside the 2^-11
 // relative rounding of the stored value) at a quarter of the instructions of erff.
 __device__ __forceinline__ float gelu_erf_h16(float v) {
-    const float x = fabsf(v) * 0.70710678118654752440f;
-    const float t = __frcp_rn(fmaf(0.3275911f, x, 1.0f));
+    // x = |v| / sqrt 2;  t = 1 / (1 + p x);  erf x = 1 - (a1 t + ... + a5 t^5) exp(-x^2)
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f * 0.70710678118654752440f, fabsf(v), 1.0f));   // v_rcp_f32 (1 ulp); a correctly rounded 1/x costs ten instructions
     float p = fmaf(1.061405429f, t, -1.453152027f);
     p = fmaf(p, t, 1.421413741f);
     p = fmaf(p, t, -0.284496736f);
     p = fmaf(p, t, 0.254829592f);
-    const float e = 1.0f - p * t * __expf(-x * x);       // erf(|v| / sqrt 2)
-    return 0.5f * v + 0.5f * fabsf(v) * e;               // 0.5 v (1 + sign(v) erf(|v|/sqrt 2))
+    p *= t;
+    const float ex = __builtin_amdgcn_exp2f((v * v) * (-0.5f * 1.44269504088896340736f));   // exp(-v^2 / 2) = 2^(-v^2 log2(e) / 2)
+    const float e = fmaf(-p, ex, 1.0f);                  // erf(|v| / sqrt 2)
+    const float h = 0.5f * v;
+    return fmaf(fabsf(h), e, h);                         // 0.5 v (1 + sign(v) erf(|v| / sqrt 2))
 }
 
 // Row -> (sample, token) mapping shared by the embedding and the epilogues.  A whole-sequence pass
