@@ -132,11 +132,14 @@ template void launch_decode_attention<f16>(const f16 *, f16 *, f16 *, f16 *, int
 // B operand of the second product O^T = V^T P^T (16 keys per instruction).
 constexpr int FA_BQ = 128, FA_BK = 64, FA_DH = 64;
 // LDS tiles are swizzled instead of padded.  K [key][d]: the 16-byte chunk c of row `key` sits in slot
-// c ^ (key & 7), so the 16-byte fragment reads of 32 consecutive rows fall on all banks.  V^T [d][key]:
+// c ^ (bits 1, 2 and 4 of key): a 16-byte read of a wave is served in four passes of 16 lanes (lanes
+// that agree in bits 3 and 5) over 64 banks, and the 16 rows of a pass - {0-7, 16-23} or {8-15, 24-31}
+// of a 32-key block - then fall on 16 different 16-byte bank groups (8 (key & 1) + slot).  V^T [d][key]:
 // key column k of row d sits at k ^ (((d >> 3) & 7) << 2): the eight rows d = 8 dc + e that one
 // transposing store instruction touches, and the rows a fragment read touches, spread over the banks,
 // while groups of four consecutive keys stay contiguous.
 constexpr int FA_KS = FA_DH;       // K tile row stride (elements)
+__device__ __forceinline__ int fa_kswz(int key) { return ((key >> 1) & 3) | (((key >> 4) & 1) << 2); }
 constexpr int FA_VS = FA_BK;       // V^T tile row stride (elements)
 
 template <typename HT>
@@ -196,7 +199,7 @@ __global__ __launch_bounds__(256, 2) void flash_attention_h16_kernel(const HT *_
         for (int r = 0; r < 2; ++r) {
             const int c = tid + r * 256;
             const int key = c >> 3, dc = c & 7;
-            *reinterpret_cast<v8 *>(&Ks[key * FA_KS + ((dc ^ (key & 7)) << 3)]) = kreg[r];
+            *reinterpret_cast<v8 *>(&Ks[key * FA_KS + ((dc ^ fa_kswz(key)) << 3)]) = kreg[r];
 #pragma unroll
             for (int e = 0; e < 8; ++e) Vt[(dc * 8 + e) * FA_VS + (key ^ (dc << 2))] = vreg[r][e];
         }
@@ -212,7 +215,7 @@ __global__ __launch_bounds__(256, 2) void flash_attention_h16_kernel(const HT *_
             for (int v = 0; v < 16; ++v) sacc[kb][v] = 0.f;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                const v8 kf = *reinterpret_cast<const v8 *>(&Ks[(32 * kb + l32) * FA_KS + (((2 * c + g) ^ (l32 & 7)) << 3)]);
+                const v8 kf = *reinterpret_cast<const v8 *>(&Ks[(32 * kb + l32) * FA_KS + (((2 * c + g) ^ fa_kswz(l32)) << 3)]);
                 sacc[kb] = Half16<HT>::mfma(kf, qf[c], sacc[kb]);
             }
         }
