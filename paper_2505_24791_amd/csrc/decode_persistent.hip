@@ -132,8 +132,9 @@ __device__ __forceinline__ void ln_prefetch(const Ctx &c, const HT *__restrict__
 // K = W = 256 S.  Hs float32 fragment-major (read through L2), Wt fragment-major, C fragment-major
 // when 16-bit, row-major [row, N] when float.  Column block cb belongs to member cb % n.
 // pre: the weights of the first round; pf(): issues the next stage's weight loads (called once the
-// activation loads of this stage are under way).
-template <typename HT, int MB, int S, int EPI, typename OutT, class PF>
+// activation loads of this stage are under way).  LOCAL: C holds the group's rows only (row 0 = the
+// group's first row), e.g. a buffer in LDS.
+template <typename HT, int MB, int S, int EPI, typename OutT, class PF, bool LOCAL = false>
 __device__ __forceinline__ void ln_gemm_stage(const Ctx &c_in, rsrc_t hs_rs, const float *__restrict__ g,
                                               const float *__restrict__ be, const HT *__restrict__ Wt,
                                               const float *__restrict__ bias, OutT *C, int N, f32x4v *red,
@@ -257,7 +258,7 @@ __device__ __forceinline__ void ln_gemm_stage(const Ctx &c_in, rsrc_t hs_rs, con
                 const float bv = first ? bv0[qi] : bias[col];
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    const int row = (c.rb0 + i) * 16 + 4 * c.kg + v;
+                    const int row = ((LOCAL ? 0 : c.rb0) + i) * 16 + 4 * c.kg + v;   // LOCAL: C is the workgroup's own buffer
                     float val = t[v] + bv;
                     if (EPI == EPI_BIAS_GELU) val = gelu_erf_h16(val);
                     if constexpr (sizeof(OutT) == 2) C[frag_off(row, col, N >> 5)] = from_f32<OutT>(val);
@@ -533,6 +534,7 @@ __global__ __launch_bounds__(P_THREADS) void seq_persistent_kernel(SeqArgs a) {
     float *wred = opart + P_NW * 64;                                          // [16]
     float *sc = wred + 16;                                                    // [2][T]
     float *wemb = sc + 2 * a.T;                                               // [P_EB][D + 1][16]: w_in slice, then b_in
+    float *pl = wemb + (size_t)P_EB * (a.D + 1) * 16;                         // [16*MB][2D]: this step's [mu | alpha] of the group's rows
 
     Ctx c;
     c.tid = threadIdx.x; c.lane = c.tid & 63; c.wave = c.tid >> 6; c.r = c.lane & 15; c.kg = c.lane >> 4;
@@ -575,11 +577,9 @@ __global__ __launch_bounds__(P_THREADS) void seq_persistent_kernel(SeqArgs a) {
     const int T = a.T, D = a.D;
     HT *qkv = reinterpret_cast<HT *>(a.qkv), *o = reinterpret_cast<HT *>(a.o), *ff = reinterpret_cast<HT *>(a.ff);
     const uint32_t ws_rows = 8u * RW_ROWS;
-    const rsrc_t hs_rs = make_rsrc(a.hs, ws_rows * W * 4u);
     const rsrc_t qkv_rs = make_rsrc(qkv, ws_rows * 3u * W * 2u);
     const rsrc_t o_rs = make_rsrc(o, ws_rows * W * 2u);
     const rsrc_t ff_rs = make_rsrc(ff, ws_rows * (uint32_t)a.ratio * W * 2u);
-    const rsrc_t p_rs = make_rsrc(a.p, ws_rows * 2u * D * 4u);
     volatile int *sh_ok = &sh[6];
     // this member's slices of the embedding matrix and bias stay in LDS for the whole block
     for (int bi = 0, cb = c.slot; bi < P_EB && cb < W / 16; ++bi, cb += c.n)
@@ -600,6 +600,8 @@ __global__ __launch_bounds__(P_THREADS) void seq_persistent_kernel(SeqArgs a) {
         }
     }
     __syncthreads();
+    Ctx ch = c;      // the head projection: every member takes every column block
+    ch.slot = 0; ch.n = 1;
 
     for (int l = 0; l < T; ++l) {
 #ifdef SJD_SEQ_TIMELINE
@@ -611,6 +613,10 @@ __global__ __launch_bounds__(P_THREADS) void seq_persistent_kernel(SeqArgs a) {
         // values were requested one step ahead
         const int tok = a.reversed ? T - 1 - l : l;
         const int tok_next = a.reversed ? T - 2 - l : l + 1;
+        // The residual stream lives in two copies that alternate with the step: the embedding of step l+1
+        // is written while slower members may still read the stream of step l for their head projection.
+        float *hs = a.hs + (size_t)(l & 1) * ws_rows * W;
+        const rsrc_t hs_rs = make_rsrc(hs, ws_rows * W * 4u);
 #pragma unroll
         for (int q = 0; q < ZPT; ++q) {
             const int e = c.tid + q * P_THREADS;
@@ -620,10 +626,7 @@ __global__ __launch_bounds__(P_THREADS) void seq_persistent_kernel(SeqArgs a) {
                 if (row < c.nrows) {
                     const size_t idx = ((size_t)(c.row0 + row) * T + tok) * D + d;
                     xn = zreg[q];
-                    if (l > 0) {
-                        const uint32_t po = (uint32_t)((c.rb0 * 16 + row) * 2 * D + d) * 4u;
-                        xn = fmaf(xn, expf(ld4_l2(p_rs, po + (uint32_t)D * 4u)), ld4_l2(p_rs, po));
-                    }
+                    if (l > 0) xn = fmaf(xn, expf(pl[row * 2 * D + D + d]), pl[row * 2 * D + d]);
                     if (c.slot == 0) a.x[idx] = xn;
                     if (l + 1 < T) zreg[q] = a.z[((size_t)(c.row0 + row) * T + tok_next) * D + d];
                 }
@@ -647,7 +650,7 @@ __global__ __launch_bounds__(P_THREADS) void seq_persistent_kernel(SeqArgs a) {
                         acc += a.b_in[col];
                         for (int d = 0; d < D; ++d) acc = fmaf(xs[row * D + d], a.w_in[(size_t)d * W + col], acc);
                     }
-                    a.hs[frag_off(c.rb0 * 16 + row, col, W / 32)] = acc;
+                    hs[frag_off(c.rb0 * 16 + row, col, W / 32)] = acc;
                 }
             }
         }
@@ -680,7 +683,7 @@ __global__ __launch_bounds__(P_THREADS) void seq_persistent_kernel(SeqArgs a) {
             if (!group_barrier(c, sh_ok)) return;
             SJD_TLC(c);
             if (!AHEAD) res_prefetch<HT, S, 1>(c, (const HT *)lw.f_o, c.slot, wo);
-            gemm_resid_stage<HT, MB, S, 1>(c, o_rs, (const HT *)lw.f_o, lw.b_o, hs_rs, a.hs, red, wo, [&]() {
+            gemm_resid_stage<HT, MB, S, 1>(c, o_rs, (const HT *)lw.f_o, lw.b_o, hs_rs, hs, red, wo, [&]() {
                 if (AHEAD) ln_prefetch<HT, S>(c, (const HT *)lw.f_fc1, 4 * W, c.slot, wln);
             });
             SJD_TLC(c);
@@ -698,18 +701,19 @@ __global__ __launch_bounds__(P_THREADS) void seq_persistent_kernel(SeqArgs a) {
             const HT *next_w = (const HT *)(last ? a.f_head : a.layers[last ? ly : ly + 1].f_qkv);
             const int next_n = last ? 2 * D : 3 * W;
             if (!AHEAD) res_prefetch<HT, S, 4>(c, (const HT *)lw.f_fc2, c.slot, wf2);
-            gemm_resid_stage<HT, MB, S, 4>(c, ff_rs, (const HT *)lw.f_fc2, lw.b_fc2, hs_rs, a.hs, red, wf2, [&]() {
-                if (AHEAD) ln_prefetch<HT, S>(c, next_w, next_n, c.slot, wln);
+            gemm_resid_stage<HT, MB, S, 4>(c, ff_rs, (const HT *)lw.f_fc2, lw.b_fc2, hs_rs, hs, red, wf2, [&]() {
+                if (AHEAD) { if (last) ln_prefetch<HT, S>(ch, next_w, next_n, 0, wln); else ln_prefetch<HT, S>(c, next_w, next_n, c.slot, wln); }
             });
             SJD_TLC(c);
             if (!group_barrier(c, sh_ok)) return;
             SJD_TLC(c);
         }
-        if (!AHEAD) ln_prefetch<HT, S>(c, (const HT *)a.f_head, 2 * D, c.slot, wln);
-        ln_gemm_stage<HT, MB, S, EPI_BIAS, float>(c, hs_rs, a.lnf_g, a.lnf_b, (const HT *)a.f_head, a.b_head, a.p, 2 * D,
-                                                 red, stat, wln, NoPrefetch());
+        // ---- head: every member computes all of [mu | alpha] for the group's rows (a few column blocks)
+        // into its own LDS, so that x_l and the next embedding follow without another group barrier
+        if (!AHEAD) ln_prefetch<HT, S>(ch, (const HT *)a.f_head, 2 * D, 0, wln);
+        ln_gemm_stage<HT, MB, S, EPI_BIAS, float, NoPrefetch, true>(ch, hs_rs, a.lnf_g, a.lnf_b, (const HT *)a.f_head, a.b_head,
+                                                                   pl, 2 * D, red, stat, wln, NoPrefetch());
         SJD_TLC(c);
-        if (!group_barrier(c, sh_ok)) return;
         SJD_TLC(c);
     }
 }
@@ -718,7 +722,7 @@ __global__ __launch_bounds__(P_THREADS) void seq_persistent_kernel(SeqArgs a) {
 
 size_t seq_persistent_lds_bytes(int MB, int T, int D) {
     size_t need = (size_t)P_NW * P_CB * MB * 64 * 16 + (size_t)P_NW * MB * 16 * 4 + (size_t)16 * MB * D * 4 +
-                  (size_t)P_NW * 64 * 4 + 16 * 4 + (size_t)2 * T * 4 + (size_t)P_EB * (D + 1) * 16 * 4;
+                  (size_t)P_NW * 64 * 4 + 16 * 4 + (size_t)2 * T * 4 + (size_t)P_EB * (D + 1) * 16 * 4 + (size_t)16 * MB * 2 * D * 4;
     const size_t one_per_cu = 84 * 1024;  // more than half of a CU's LDS: exactly one workgroup per CU
     if (need < one_per_cu) need = one_per_cu;
     return (need + 255) & ~(size_t)255;

@@ -572,7 +572,7 @@ int sjd_flow_create(const sjd_config *cfg, sjd_flow **out) {
     f->cfg = c;
     f->device = dev;
     const size_t T = c.seq_len, W = c.width, D = c.token_dim, R = c.mlp_ratio, B = c.max_batch, N = c.n_layers;
-    const size_t M = B * T > 256 ? B * T : 256, ab = act_bytes(f);  // the single-token paths work on up to 8 x 32 rows
+    const size_t M = B * T > 512 ? B * T : 512, ab = act_bytes(f);  // the single-token paths work on up to 8 x 32 rows; the persistent kernel keeps two copies of its residual stream
     int rc = SJD_OK;
     auto A = [&](void **p, size_t n) { if (rc == SJD_OK) rc = dev_alloc(f, p, n); };
     A((void **)&f->blob, (size_t)c.n_blocks * block_floats(c) * sizeof(float));
