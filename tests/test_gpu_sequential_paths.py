@@ -78,3 +78,24 @@ def test_persistent_path_is_refused_outside_its_coverage(torch_cuda):
     with pytest.raises(sjd.SjdError):
         f.set_sequential_path(4)
     f.close()
+
+
+def test_persistent_kernel_gives_the_same_bits_with_fewer_workgroups(torch_cuda):
+    """The persistent kernel forms its groups from the workgroups that are there: with 128 or 64
+    workgroups (16 or 8 members per XCD, each taking more columns) every row still gets the same bits."""
+    import paper_2505_24791_amd as sjd
+    torch = torch_cuda
+    cfg = wl.FlowConfig("fewer", n_blocks=2, n_layers=2, width=512, n_heads=8, seq_len=21, token_dim=12, batch=37, bf16=True)
+    blob = wl.make_weights(cfg, perturb_affine=True)
+    zd = torch.from_numpy(wl.make_latent(cfg, seed=43)).cuda()
+    f = sjd.Flow(cfg)
+    f.load_weights(blob)
+    f.set_sequential_path(2)
+    for j in range(cfg.n_blocks):
+        f.set_sequential_cus(0)
+        ref = f.sequential_inverse_block(j, zd)
+        for n in (128, 64):
+            print(f"block {j}, {n} workgroups", flush=True)
+            f.set_sequential_cus(n)
+            assert torch.equal(f.sequential_inverse_block(j, zd), ref), (j, n)
+    f.close()
