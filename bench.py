@@ -49,6 +49,9 @@ def parse():
                     help="schedule of sequential blocks: 0 automatic, 1 per-step launches replayed as a graph, 2 "
                          "persistent kernel (cooperative launch), 3 persistent kernel with an ordinary launch (for "
                          "runs under rocprofv3, which does not survive cooperative launches here)")
+    ap.add_argument("--proj-path", type=int, default=0, choices=(0, 1, 2),
+                    help="projection kernels of the whole-sequence passes: 0 automatic, 1 tile kernels with separate "
+                         "LayerNorm launches, 2 activation-stationary kernels (16-bit flows of width 512)")
     ap.add_argument("--pipeline-cus", type=int, default=-1,
                     help="also time the steps with two batches in flight: the sequential block of one batch on this "
                          "many CUs (a multiple of 32) beside the Jacobi blocks of the previous batch on the rest; "
@@ -100,6 +103,7 @@ def main() -> int:
     flow = sjd.Flow(cfg)
     flow.load_weights(blob)
     flow.set_sequential_path(args.seq_path)
+    flow.set_projection_path(args.proj_path)
     z = torch.from_numpy(z_host).cuda()
     x = torch.empty_like(z)
     opts = sjd.JacobiOpts(tau=tau, criterion=args.criterion, init=args.init,

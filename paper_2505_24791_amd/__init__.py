@@ -25,7 +25,8 @@ PROF_NAMES = ("gemm", "attention", "epilogue", "decode_gemm", "decode_attn", "ot
 
 EXPORTS = ("sjd_flow_create", "sjd_flow_load_weights", "sjd_jacobi_inverse_block", "sjd_sequential_inverse_block",
            "sjd_sample", "sjd_conditioner", "sjd_op_linear_h16", "sjd_jacobi_trace_block", "sjd_forward_block",
-           "sjd_forward", "sjd_flow_set_mask_nearest", "sjd_flow_set_sequential_path", "sjd_flow_set_sequential_cus", "sjd_profile_enable", "sjd_profile_read", "sjd_flow_device_bytes",
+           "sjd_forward", "sjd_flow_set_mask_nearest", "sjd_flow_set_sequential_path", "sjd_flow_set_sequential_cus", "sjd_flow_set_projection_path",
+           "sjd_op_panel_linear_h16", "sjd_profile_enable", "sjd_profile_read", "sjd_flow_device_bytes",
            "sjd_last_error", "sjd_flow_destroy")
 
 
@@ -144,6 +145,27 @@ def op_linear_h16(a, wt, bias, M, N, K, epilogue, *, resid=None, kernel=0):
     _check(lib.sjd_op_linear_h16(dtype, kernel, C.c_void_p(a.data_ptr()), C.c_void_p(wt.data_ptr()),
                                  C.c_void_p(bias.data_ptr()), C.c_void_p(resid.data_ptr()) if resid is not None else None,
                                  C.c_void_p(c.data_ptr()) if c is not None else None, M, N, K, epilogue, _stream_ptr()))
+    return resid if epilogue == 2 else c
+
+
+def op_panel_linear_h16(a, wt, bias, M, N, epilogue, *, ln_g=None, ln_b=None, resid=None):
+    """``sjd_op_panel_linear_h16`` on torch tensors (K = 512).  epilogue 0 / 1: a [M,512] float32, ln_g / ln_b
+    [512] float32, returns c [M,N] in wt's type; epilogue 2: a [M,512] 16-bit, updates ``resid`` in place."""
+    import torch
+    lib = load_library()
+    assert a.is_cuda and wt.is_cuda and a.is_contiguous() and wt.is_contiguous() and tuple(a.shape) == (M, 512)
+    assert wt.shape[0] >= N and wt.shape[1] == 512 and wt.dtype in (torch.float16, torch.bfloat16)
+    dtype = DTYPE_F16 if wt.dtype == torch.float16 else DTYPE_BF16
+    c = None
+    if epilogue == 2:
+        assert a.dtype == wt.dtype
+        assert resid is not None and resid.dtype == torch.float32 and tuple(resid.shape) == (M, N) and resid.is_contiguous()
+    else:
+        assert a.dtype == torch.float32 and ln_g is not None and ln_b is not None
+        c = torch.empty((M, N), dtype=wt.dtype, device=a.device)
+    ptr = lambda t: C.c_void_p(t.data_ptr()) if t is not None else None
+    _check(lib.sjd_op_panel_linear_h16(dtype, ptr(a), ptr(ln_g), ptr(ln_b), ptr(wt), ptr(bias), ptr(resid), ptr(c), M, N,
+                                       epilogue, _stream_ptr()))
     return resid if epilogue == 2 else c
 
 
@@ -280,6 +302,10 @@ class Flow:
     def set_sequential_path(self, path: int) -> None:
         """0 automatic, 1 per-step launches (graph replay), 2 persistent kernel, 3 the same with a plain launch."""
         _check(self.lib.sjd_flow_set_sequential_path(self._h, path))
+
+    def set_projection_path(self, path: int) -> None:
+        """0 automatic, 1 tile kernels + LayerNorm launches, 2 activation-stationary kernels (16-bit, width 512)."""
+        _check(self.lib.sjd_flow_set_projection_path(self._h, path))
 
     def set_sequential_cus(self, n_cus: int) -> None:
         """Workgroups of the persistent sequential kernel: 0 = one per CU of the device, else a multiple of 32."""

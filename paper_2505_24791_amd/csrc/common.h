@@ -78,6 +78,15 @@ __device__ __forceinline__ size_t frag_off(int row, int k, int KS) {
 
 __device__ __forceinline__ float gelu_erf(float v) { return 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f)); }
 
+// A float32 value that is about to be rounded to 16 bits, made opaque to the compiler.  Otherwise it
+// folds the fma that produces the value into the conversion (v_fma_mix: one rounding instead of
+// two) for some elements of an unrolled loop and not for others, and two kernels that compute the
+// same thing differ in the last bit of a few results per hundred thousand.
+__device__ __forceinline__ float keep_f32(float v) {
+    asm("" : "+v"(v));
+    return v;
+}
+
 // GELU (erf form) for results that are stored in 16 bits: erf by the rational-times-exponential
 // formula 7.1.26 of Abramowitz & Stegun (absolute error below 1.5e-7, far inside the 2^-11
 // relative rounding of the stored value) at a quarter of the instructions of erff.
@@ -92,7 +101,7 @@ __device__ __forceinline__ float gelu_erf_h16(float v) {
     const float ex = __builtin_amdgcn_exp2f((v * v) * (-0.5f * 1.44269504088896340736f));   // exp(-v^2 / 2) = 2^(-v^2 log2(e) / 2)
     const float e = fmaf(-p, ex, 1.0f);                  // erf(|v| / sqrt 2)
     const float h = 0.5f * v;
-    return fmaf(fabsf(h), e, h);                         // 0.5 v (1 + sign(v) erf(|v| / sqrt 2))
+    return keep_f32(fmaf(fabsf(h), e, h));               // 0.5 v (1 + sign(v) erf(|v| / sqrt 2))
 }
 
 // Row -> (sample, token) mapping shared by the embedding and the epilogues.  A whole-sequence pass
@@ -134,6 +143,20 @@ void launch_gemm_f32(const float *A, const float *B, const float *bias, const fl
 template <typename HT, typename OutT>
 void launch_gemm_h16(const HT *A, const HT *Bt, const float *bias, const float *resid, OutT *C, int M, int N, int K,
                      Epi epi, hipStream_t s, int kernel = 0);
+
+// Activation-stationary projections for K = 512 (gemm_panel.hip).  Wf: the weight in the fragment order of
+// the 32x32x16 instruction (launch_weights_to_panel_frag from the transposed [N, 512] copy; N % 256 == 0).
+//   launch_ln_gemm_panel:    C[M,N] (16-bit) = epi(LayerNorm(H[M,512]; g, b) * W + bias), epi = EPI_BIAS or EPI_BIAS_GELU
+//   launch_gemm_panel_resid: H[M,N] (float32) += A[M,512] * W + bias
+// Bit-identical to launch_layernorm + launch_gemm_h16.  gemm_panel_applicable: the shape is covered
+// (out_bytes: element size of the output).
+bool gemm_panel_applicable(int M, int N, int K, int out_bytes);
+template <typename HT> void launch_weights_to_panel_frag(const HT *wt, HT *dst, int N, hipStream_t s);
+template <typename HT>
+void launch_ln_gemm_panel(const float *H, const float *g, const float *b, const HT *Wf, const float *bias, HT *C, int M,
+                          int N, Epi epi, hipStream_t s);
+template <typename HT>
+void launch_gemm_panel_resid(const HT *A, const HT *Wf, const float *bias, float *H, int M, int N, hipStream_t s);
 
 // Causal attention, one wave per (sample, head, query row); works for any shape and both types.
 // q rows: q + (sample*q_rows_per_sample + r) * q_stride; row r (processing position t0 + r) attends

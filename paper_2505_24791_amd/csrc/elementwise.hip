@@ -85,7 +85,7 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const float *__restrict_
     for (int i = lane; i < W; i += 64) { float d = xr[i] - mean; v = fmaf(d, d, v); }
     const float rstd = 1.0f / sqrtf(wave_sum(v) / (float)W + 1e-5f);
     OutT *yr = y + (size_t)row * W;
-    for (int i = lane; i < W; i += 64) yr[i] = from_f32<OutT>((xr[i] - mean) * rstd * g[i] + b[i]);
+    for (int i = lane; i < W; i += 64) yr[i] = from_f32<OutT>(keep_f32((xr[i] - mean) * rstd * g[i] + b[i]));
 }
 
 // The same for widths that are multiples of 256: the row is read once, 16 bytes per lane and load,
@@ -119,7 +119,7 @@ __global__ __launch_bounds__(256) void layernorm_vec_kernel(const float *__restr
         const f32x4 b4 = reinterpret_cast<const f32x4 *>(b)[k * 64 + lane];
         f32x4 o;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = (v[k][e] - mean) * rstd * g4[e] + b4[e];
+        for (int e = 0; e < 4; ++e) o[e] = keep_f32((v[k][e] - mean) * rstd * g4[e] + b4[e]);
         if constexpr (sizeof(OutT) == 4) {
             reinterpret_cast<f32x4 *>(yr)[k * 64 + lane] = o;
         } else {

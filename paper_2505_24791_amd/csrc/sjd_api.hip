@@ -41,6 +41,7 @@ struct LayerW {
     const float *w_qkv, *w_o, *w_fc1, *w_fc2;      // float32 [in, out] (views into the device blob)
     void *t_qkv, *t_o, *t_fc1, *t_fc2;             // 16-bit transposed [out (padded), in]
     void *f_qkv, *f_o, *f_fc1, *f_fc2;             // 16-bit fragment-major copies for single-token steps
+    void *p_qkv = nullptr, *p_o = nullptr, *p_fc1 = nullptr;   // 32x32x16 fragment order for the panel kernels (W = 512)
 };
 struct BlockW {
     const float *w_in, *b_in, *pos, *lnf_g, *lnf_b, *w_head, *b_head;
@@ -63,6 +64,8 @@ struct sjd_flow {
     float *blob = nullptr;       // whole float32 blob on the device
     void *arena = nullptr;       // transposed 16-bit matrices
     void *arena_frag = nullptr;  // the same matrices in fragment-major order (sequential fast path)
+    void *arena_panel = nullptr; // QKV, attention-output and MLP-input matrices in the panel kernels' order
+    int proj_path = 0;           // 0 automatic, 1 tile kernels only, 2 panel kernels wherever they apply
     std::vector<BlockW> block;
     // workspaces (element type depends on dtype: float or bf16 for a, qkv, o, f and the cache)
     float *h = nullptr, *p = nullptr;
@@ -113,6 +116,11 @@ size_t block_floats(const sjd_config &c) {
 }
 
 constexpr size_t kNPad = 256;  // transposed weights are padded to this many rows per matrix
+
+// the panel projection kernels cover 16-bit flows of width 512 whose matrices have multiples of 256 columns
+bool panel_ok(const sjd_config &c) {
+    return c.dtype != SJD_DTYPE_F32 && c.width == 512 && ((size_t)c.mlp_ratio * c.width) % 256 == 0;
+}
 
 size_t arena_elems_per_block(const sjd_config &c) {
     size_t W = c.width, R = c.mlp_ratio, D = c.token_dim;
@@ -194,6 +202,24 @@ void layernorm(sjd_flow *f, const float *x, const float *g, const float *b, void
     else launch_layernorm<float>(x, g, b, (float *)y, rows, W, s);
 }
 
+// LayerNorm + projection in one launch (16-bit flows of width 512): C = epi(LayerNorm(H) W + bias)
+void ln_project_panel(sjd_flow *f, const float *H, const float *g, const float *b, const void *wf, const float *bias,
+                      void *C, int M, int N, Epi epi, hipStream_t s) {
+    const int W = f->cfg.width;
+    ProfScope ps(f, SJD_PROF_GEMM, 2.0 * M * (double)N * W, (double)M * W * 4.0 + (double)W * N * 2.0 + (double)M * N * 2.0 + N * 4.0, s);
+    if (f->cfg.dtype == SJD_DTYPE_BF16) launch_ln_gemm_panel<bf16>(H, g, b, (const bf16 *)wf, bias, (bf16 *)C, M, N, epi, s);
+    else launch_ln_gemm_panel<f16>(H, g, b, (const f16 *)wf, bias, (f16 *)C, M, N, epi, s);
+}
+
+// H += A W + bias on the panel kernel
+void project_panel_resid(sjd_flow *f, const void *A, const void *wf, const float *bias, float *H, int M, int N,
+                         hipStream_t s) {
+    const int W = f->cfg.width;
+    ProfScope ps(f, SJD_PROF_GEMM, 2.0 * M * (double)N * W, (double)M * W * 2.0 + (double)W * N * 2.0 + (double)M * N * 8.0 + N * 4.0, s);
+    if (f->cfg.dtype == SJD_DTYPE_BF16) launch_gemm_panel_resid<bf16>((const bf16 *)A, (const bf16 *)wf, bias, H, M, N, s);
+    else launch_gemm_panel_resid<f16>((const f16 *)A, (const f16 *)wf, bias, H, M, N, s);
+}
+
 // whole-sequence causal attention on the fused qkv buffer [n*T, 3W] -> o [n*T, W]
 template <typename AT>
 void attention_full(const void *qkv, void *o, int n, int T, int W, int H, int mask_o, hipStream_t s) {
@@ -226,10 +252,20 @@ void conditioner_pass(sjd_flow *f, int j, const float *x, int n, const int32_t *
         ProfScope ps(f, SJD_PROF_OTHER, 2.0 * M * (double)D * W, (double)M * W * 4, s);
         launch_embed(x, bw.w_in, bw.b_in, bw.pos, f->h, M, D, W, RowMap{active, T, 0, T, rev}, s);
     }
+    // Width 512: LayerNorm + projection in one activation-stationary launch where that is faster: a
+    // workgroup of those kernels is 128 rows x 768..1024 columns of work, so below ~90 panels the tile
+    // kernels' finer grain wins (measured on configuration C2: QKV from 10240 rows on, MLP input from 12288)
+    const bool panel_any = f->arena_panel && f->proj_path != 1 && gemm_panel_applicable(M, RW, W, 2) &&
+                           gemm_panel_applicable(M, 3 * W, W, 2) && gemm_panel_applicable(M, W, W, 4);
+    const bool panel_qkv = panel_any && (f->proj_path == 2 || M >= 10240);
+    const bool panel_fc1 = panel_any && (f->proj_path == 2 || M >= 12288);
     for (int l = 0; l < c.n_layers; ++l) {
         const LayerW &lw = bw.layer[l];
-        layernorm(f, f->h, lw.ln1_g, lw.ln1_b, f->a, M, s);
-        project(f, SJD_PROF_GEMM, f->a, lw.w_qkv, lw.t_qkv, lw.b_qkv, f->qkv, M, 3 * W, W, EPI_BIAS, false, s);
+        if (panel_qkv) ln_project_panel(f, f->h, lw.ln1_g, lw.ln1_b, lw.p_qkv, lw.b_qkv, f->qkv, M, 3 * W, EPI_BIAS, s);
+        else {
+            layernorm(f, f->h, lw.ln1_g, lw.ln1_b, f->a, M, s);
+            project(f, SJD_PROF_GEMM, f->a, lw.w_qkv, lw.t_qkv, lw.b_qkv, f->qkv, M, 3 * W, W, EPI_BIAS, false, s);
+        }
         {
             const double ab = act_bytes(f);
             ProfScope ps(f, SJD_PROF_ATTENTION, 2.0 * n * (double)T * (T + 1) * W, (double)M * 4 * W * ab, s);
@@ -237,9 +273,13 @@ void conditioner_pass(sjd_flow *f, int j, const float *x, int n, const int32_t *
             else if (c.dtype == SJD_DTYPE_F16) attention_full<f16>(f->qkv, f->o, n, T, W, H, f->mask_nearest, s);
             else attention_full<float>(f->qkv, f->o, n, T, W, H, f->mask_nearest, s);
         }
-        project(f, SJD_PROF_GEMM, f->o, lw.w_o, lw.t_o, lw.b_o, f->h, M, W, W, EPI_BIAS_RESIDUAL, true, s);
-        layernorm(f, f->h, lw.ln2_g, lw.ln2_b, f->a, M, s);
-        project(f, SJD_PROF_GEMM, f->a, lw.w_fc1, lw.t_fc1, lw.b_fc1, f->f, M, RW, W, EPI_BIAS_GELU, false, s);
+        if (panel_qkv) project_panel_resid(f, f->o, lw.p_o, lw.b_o, f->h, M, W, s);
+        else project(f, SJD_PROF_GEMM, f->o, lw.w_o, lw.t_o, lw.b_o, f->h, M, W, W, EPI_BIAS_RESIDUAL, true, s);
+        if (panel_fc1) ln_project_panel(f, f->h, lw.ln2_g, lw.ln2_b, lw.p_fc1, lw.b_fc1, f->f, M, RW, EPI_BIAS_GELU, s);
+        else {
+            layernorm(f, f->h, lw.ln2_g, lw.ln2_b, f->a, M, s);
+            project(f, SJD_PROF_GEMM, f->a, lw.w_fc1, lw.t_fc1, lw.b_fc1, f->f, M, RW, W, EPI_BIAS_GELU, false, s);
+        }
         project(f, SJD_PROF_GEMM, f->f, lw.w_fc2, lw.t_fc2, lw.b_fc2, f->h, M, W, RW, EPI_BIAS_RESIDUAL, true, s);
     }
     layernorm(f, f->h, bw.lnf_g, bw.lnf_b, f->a, M, s);
@@ -578,6 +618,7 @@ int sjd_flow_create(const sjd_config *cfg, sjd_flow **out) {
     A((void **)&f->blob, (size_t)c.n_blocks * block_floats(c) * sizeof(float));
     if (c.dtype != SJD_DTYPE_F32) A(&f->arena, (size_t)c.n_blocks * arena_elems_per_block(c) * 2);
     if (fast_decode_ok(f)) A(&f->arena_frag, (size_t)c.n_blocks * arena_elems_per_block(c) * 2);
+    if (panel_ok(c)) A(&f->arena_panel, (size_t)c.n_blocks * c.n_layers * (3 * W + W + R * W) * W * 2);
     A((void **)&f->h, M * W * 4);
     A((void **)&f->p, M * 2 * D * 4);
     A(&f->a, M * W * ab);
@@ -664,6 +705,15 @@ int sjd_flow_load_weights(sjd_flow *f, const void *host_blob, size_t nbytes) {
         arf += rows * K * 2;
         return dst;
     };
+    char *arp = (char *)f->arena_panel;
+    auto prep_panel = [&](const void *wt, size_t N) -> void * {   // from the transposed 16-bit copy
+        if (!f->arena_panel) return nullptr;
+        void *dst = arp;
+        if (dt == SJD_DTYPE_BF16) launch_weights_to_panel_frag<bf16>((const bf16 *)wt, (bf16 *)dst, (int)N, 0);
+        else launch_weights_to_panel_frag<f16>((const f16 *)wt, (f16 *)dst, (int)N, 0);
+        arp += N * W * 2;
+        return dst;
+    };
     for (int j = 0; j < c.n_blocks; ++j) {
         const float *p = f->blob + (size_t)j * bf;
         BlockW &bw = f->block[j];
@@ -693,6 +743,9 @@ int sjd_flow_load_weights(sjd_flow *f, const void *host_blob, size_t nbytes) {
             lw.f_o = prep_frag(lw.w_o, W, W);
             lw.f_fc1 = prep_frag(lw.w_fc1, W, R * W);
             lw.f_fc2 = prep_frag(lw.w_fc2, R * W, W);
+            lw.p_qkv = prep_panel(lw.t_qkv, 3 * W);
+            lw.p_o = prep_panel(lw.t_o, W);
+            lw.p_fc1 = prep_panel(lw.t_fc1, R * W);
         }
         bw.lnf_g = p; p += W;
         bw.lnf_b = p; p += W;
@@ -883,11 +936,48 @@ int sjd_op_linear_h16(int dtype, int kernel, const void *a_dev, const void *wt_d
     return SJD_OK;
 }
 
+int sjd_op_panel_linear_h16(int dtype, const void *a_dev, const float *ln_g_dev, const float *ln_b_dev,
+                            const void *wt_dev, const float *bias_dev, float *resid_out_dev, void *c_dev, int M, int N,
+                            int epilogue, void *hip_stream) {
+    if (!a_dev || !wt_dev || !bias_dev) return fail(SJD_EINVAL, "null device pointer");
+    if (dtype != SJD_DTYPE_BF16 && dtype != SJD_DTYPE_F16) return fail(SJD_EINVAL, "dtype must be a 16-bit mode");
+    if (epilogue < 0 || epilogue > 2) return fail(SJD_EINVAL, "epilogue must be 0..2");
+    if (epilogue == 2 ? !resid_out_dev : (!c_dev || !ln_g_dev || !ln_b_dev)) return fail(SJD_EINVAL, "null device pointer");
+    if (!gemm_panel_applicable(M, N, 512, epilogue == 2 ? 4 : 2))
+        return fail(SJD_EINVAL, "the panel kernels need M >= 1, N a multiple of 256 and an output below 2 GiB");
+    if (epilogue == 2 && N > 512) return fail(SJD_EINVAL, "the residual variant covers N <= 512");
+    hipStream_t s = (hipStream_t)hip_stream;
+    void *wf = nullptr;
+    HIP_TRY(hipMalloc(&wf, (size_t)N * 512 * 2));
+    if (dtype == SJD_DTYPE_BF16) {
+        launch_weights_to_panel_frag<bf16>((const bf16 *)wt_dev, (bf16 *)wf, N, s);
+        if (epilogue == 2) launch_gemm_panel_resid<bf16>((const bf16 *)a_dev, (const bf16 *)wf, bias_dev, resid_out_dev, M, N, s);
+        else launch_ln_gemm_panel<bf16>((const float *)a_dev, ln_g_dev, ln_b_dev, (const bf16 *)wf, bias_dev, (bf16 *)c_dev, M, N, (Epi)epilogue, s);
+    } else {
+        launch_weights_to_panel_frag<f16>((const f16 *)wt_dev, (f16 *)wf, N, s);
+        if (epilogue == 2) launch_gemm_panel_resid<f16>((const f16 *)a_dev, (const f16 *)wf, bias_dev, resid_out_dev, M, N, s);
+        else launch_ln_gemm_panel<f16>((const float *)a_dev, ln_g_dev, ln_b_dev, (const f16 *)wf, bias_dev, (f16 *)c_dev, M, N, (Epi)epilogue, s);
+    }
+    const hipError_t e1 = hipStreamSynchronize(s), e2 = hipGetLastError();
+    (void)hipFree(wf);
+    HIP_TRY(e1);
+    HIP_TRY(e2);
+    return SJD_OK;
+}
+
 #ifdef SJD_SEQ_TIMELINE
 extern "C" __attribute__((visibility("default"))) int sjd_debug_read_sync(sjd_flow *f, int *out1024) {
     return hipMemcpy(out1024, f->psync, 1024 * sizeof(int), hipMemcpyDeviceToHost) == hipSuccess ? 0 : -1;
 }
 #endif
+
+int sjd_flow_set_projection_path(sjd_flow *f, int path) {
+    if (!f) return fail(SJD_EINVAL, "null flow");
+    if (path < 0 || path > 2) return fail(SJD_EINVAL, "the projection path must be 0 (automatic), 1 (tile kernels) or 2 (panel kernels)");
+    if (path == 2 && !f->arena_panel) return fail(SJD_EINVAL, "the panel kernels cover 16-bit flows of width 512 only");
+    f->proj_path = path;
+    return SJD_OK;
+}
 
 int sjd_flow_set_mask_nearest(sjd_flow *f, int o) {
     if (!f) return fail(SJD_EINVAL, "null flow");
