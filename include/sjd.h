@@ -194,16 +194,17 @@ SJD_API int sjd_op_linear_h16(int dtype, int kernel, const void *a_dev, const vo
                               float *resid_out_dev, void *c_dev, int M, int N, int K, int epilogue, void *hip_stream);
 
 /* The same building block on the activation-stationary kernels that 16-bit flows of width 512 use for
- * their whole-sequence passes (K = 512 only; N a multiple of 256), exported for the same reason.
- * epilogue 0 / 1: a_dev is the float32 residual stream [M, 512]; the op computes
+ * their whole-sequence passes (N a multiple of 256), exported for the same reason.
+ * epilogue 0 / 1 (K = 512): a_dev is the float32 residual stream [M, 512]; the op computes
  * c_dev [M, N] 16-bit = epi(LayerNorm(a; ln_g_dev, ln_b_dev [512] float32, eps 1e-5) W + bias) - LayerNorm
- * is part of the launch.  epilogue 2: a_dev is [M, 512] 16-bit, resid_out_dev [M, N] float32 += A W + bias
- * (ln pointers unused).  wt_dev as for sjd_op_linear_h16 ([N, 512] transposed 16-bit); the op makes a
- * temporary device copy of it in the kernels' fragment order (it allocates and frees N KB).
- * All pointers are DEVICE memory.  SJD_EINVAL for shapes outside the kernels' range. */
+ * is part of the launch.  epilogue 2 (K a multiple of 512): a_dev is [M, K] 16-bit, resid_out_dev [M, N]
+ * float32 += A W + bias (ln pointers unused); K = 512 runs the panel kernel (N <= 512), K > 512 the kernel
+ * that streams the left operand through LDS.  wt_dev as for sjd_op_linear_h16 ([N, K] transposed 16-bit);
+ * the op makes a temporary device copy of it in the kernels' fragment order (it allocates and frees
+ * 2 N K bytes).  All pointers are DEVICE memory.  SJD_EINVAL for shapes outside the kernels' range. */
 SJD_API int sjd_op_panel_linear_h16(int dtype, const void *a_dev, const float *ln_g_dev, const float *ln_b_dev,
                                     const void *wt_dev, const float *bias_dev, float *resid_out_dev, void *c_dev, int M,
-                                    int N, int epilogue, void *hip_stream);
+                                    int N, int K, int epilogue, void *hip_stream);
 
 /* Which kernels the whole-sequence passes of a 16-bit flow use for their projections: 0 automatic (the
  * activation-stationary kernels for width 512 from 2048 rows on, the tile kernels otherwise), 1 tile

@@ -148,13 +148,13 @@ def op_linear_h16(a, wt, bias, M, N, K, epilogue, *, resid=None, kernel=0):
     return resid if epilogue == 2 else c
 
 
-def op_panel_linear_h16(a, wt, bias, M, N, epilogue, *, ln_g=None, ln_b=None, resid=None):
-    """``sjd_op_panel_linear_h16`` on torch tensors (K = 512).  epilogue 0 / 1: a [M,512] float32, ln_g / ln_b
-    [512] float32, returns c [M,N] in wt's type; epilogue 2: a [M,512] 16-bit, updates ``resid`` in place."""
+def op_panel_linear_h16(a, wt, bias, M, N, epilogue, *, K=512, ln_g=None, ln_b=None, resid=None):
+    """``sjd_op_panel_linear_h16`` on torch tensors.  epilogue 0 / 1 (K = 512): a [M,512] float32, ln_g / ln_b
+    [512] float32, returns c [M,N] in wt's type; epilogue 2: a [M,K] 16-bit, updates ``resid`` in place."""
     import torch
     lib = load_library()
-    assert a.is_cuda and wt.is_cuda and a.is_contiguous() and wt.is_contiguous() and tuple(a.shape) == (M, 512)
-    assert wt.shape[0] >= N and wt.shape[1] == 512 and wt.dtype in (torch.float16, torch.bfloat16)
+    assert a.is_cuda and wt.is_cuda and a.is_contiguous() and wt.is_contiguous() and tuple(a.shape) == (M, K)
+    assert wt.shape[0] >= N and wt.shape[1] == K and wt.dtype in (torch.float16, torch.bfloat16)
     dtype = DTYPE_F16 if wt.dtype == torch.float16 else DTYPE_BF16
     c = None
     if epilogue == 2:
@@ -164,7 +164,7 @@ def op_panel_linear_h16(a, wt, bias, M, N, epilogue, *, ln_g=None, ln_b=None, re
         assert a.dtype == torch.float32 and ln_g is not None and ln_b is not None
         c = torch.empty((M, N), dtype=wt.dtype, device=a.device)
     ptr = lambda t: C.c_void_p(t.data_ptr()) if t is not None else None
-    _check(lib.sjd_op_panel_linear_h16(dtype, ptr(a), ptr(ln_g), ptr(ln_b), ptr(wt), ptr(bias), ptr(resid), ptr(c), M, N,
+    _check(lib.sjd_op_panel_linear_h16(dtype, ptr(a), ptr(ln_g), ptr(ln_b), ptr(wt), ptr(bias), ptr(resid), ptr(c), M, N, K,
                                        epilogue, _stream_ptr()))
     return resid if epilogue == 2 else c
 

@@ -158,6 +158,15 @@ void launch_ln_gemm_panel(const float *H, const float *g, const float *b, const 
 template <typename HT>
 void launch_gemm_panel_resid(const HT *A, const HT *Wf, const float *bias, float *H, int M, int N, hipStream_t s);
 
+// Residual projection for long k (gemm_stream.hip): H[M,N] (float32) += A[M,K] * W + bias with the left operand
+// streamed through LDS in chunks of 256 k and the weights in the fragment order of the 32x32x16 instruction
+// (launch_weights_to_frag32 from the transposed [N, K] copy).  K % 512 == 0, N % 256 == 0; bit-identical to
+// launch_gemm_h16.
+bool gemm_stream_applicable(int M, int N, int K);
+template <typename HT> void launch_weights_to_frag32(const HT *wt, HT *dst, int N, int K, hipStream_t s);
+template <typename HT>
+void launch_gemm_stream_resid(const HT *A, const HT *Wf, const float *bias, float *H, int M, int N, int K, hipStream_t s);
+
 // Causal attention, one wave per (sample, head, query row); works for any shape and both types.
 // q rows: q + (sample*q_rows_per_sample + r) * q_stride; row r (processing position t0 + r) attends
 // keys 0..t0+r-mask_o found at k + sample_index*kv_sample_stride + key*kv_stride (+ head*dh); same for v.

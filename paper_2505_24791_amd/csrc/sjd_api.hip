@@ -41,7 +41,7 @@ struct LayerW {
     const float *w_qkv, *w_o, *w_fc1, *w_fc2;      // float32 [in, out] (views into the device blob)
     void *t_qkv, *t_o, *t_fc1, *t_fc2;             // 16-bit transposed [out (padded), in]
     void *f_qkv, *f_o, *f_fc1, *f_fc2;             // 16-bit fragment-major copies for single-token steps
-    void *p_qkv = nullptr, *p_o = nullptr, *p_fc1 = nullptr;   // 32x32x16 fragment order for the panel kernels (W = 512)
+    void *p_qkv = nullptr, *p_o = nullptr, *p_fc1 = nullptr, *p_fc2 = nullptr;   // 32x32x16 fragment order for the panel / streaming kernels (W = 512)
 };
 struct BlockW {
     const float *w_in, *b_in, *pos, *lnf_g, *lnf_b, *w_head, *b_head;
@@ -259,6 +259,7 @@ void conditioner_pass(sjd_flow *f, int j, const float *x, int n, const int32_t *
                            gemm_panel_applicable(M, 3 * W, W, 2) && gemm_panel_applicable(M, W, W, 4);
     const bool panel_qkv = panel_any && (f->proj_path == 2 || M >= 10240);
     const bool panel_fc1 = panel_any && (f->proj_path == 2 || M >= 12288);
+    const bool stream_fc2 = panel_any && (f->proj_path == 2 || M >= 10240) && gemm_stream_applicable(M, W, RW);
     for (int l = 0; l < c.n_layers; ++l) {
         const LayerW &lw = bw.layer[l];
         if (panel_qkv) ln_project_panel(f, f->h, lw.ln1_g, lw.ln1_b, lw.p_qkv, lw.b_qkv, f->qkv, M, 3 * W, EPI_BIAS, s);
@@ -280,7 +281,11 @@ void conditioner_pass(sjd_flow *f, int j, const float *x, int n, const int32_t *
             layernorm(f, f->h, lw.ln2_g, lw.ln2_b, f->a, M, s);
             project(f, SJD_PROF_GEMM, f->a, lw.w_fc1, lw.t_fc1, lw.b_fc1, f->f, M, RW, W, EPI_BIAS_GELU, false, s);
         }
-        project(f, SJD_PROF_GEMM, f->f, lw.w_fc2, lw.t_fc2, lw.b_fc2, f->h, M, W, RW, EPI_BIAS_RESIDUAL, true, s);
+        if (stream_fc2) {
+            ProfScope ps(f, SJD_PROF_GEMM, 2.0 * M * (double)W * RW, (double)M * RW * 2.0 + (double)RW * W * 2.0 + (double)M * W * 8.0 + W * 4.0, s);
+            if (c.dtype == SJD_DTYPE_BF16) launch_gemm_stream_resid<bf16>((const bf16 *)f->f, (const bf16 *)lw.p_fc2, lw.b_fc2, f->h, M, W, RW, s);
+            else launch_gemm_stream_resid<f16>((const f16 *)f->f, (const f16 *)lw.p_fc2, lw.b_fc2, f->h, M, W, RW, s);
+        } else project(f, SJD_PROF_GEMM, f->f, lw.w_fc2, lw.t_fc2, lw.b_fc2, f->h, M, W, RW, EPI_BIAS_RESIDUAL, true, s);
     }
     layernorm(f, f->h, bw.lnf_g, bw.lnf_b, f->a, M, s);
     project(f, SJD_PROF_GEMM, f->a, bw.w_head, bw.t_head, bw.b_head, f->p, M, 2 * D, W, EPI_BIAS, true, s);
@@ -618,7 +623,7 @@ int sjd_flow_create(const sjd_config *cfg, sjd_flow **out) {
     A((void **)&f->blob, (size_t)c.n_blocks * block_floats(c) * sizeof(float));
     if (c.dtype != SJD_DTYPE_F32) A(&f->arena, (size_t)c.n_blocks * arena_elems_per_block(c) * 2);
     if (fast_decode_ok(f)) A(&f->arena_frag, (size_t)c.n_blocks * arena_elems_per_block(c) * 2);
-    if (panel_ok(c)) A(&f->arena_panel, (size_t)c.n_blocks * c.n_layers * (3 * W + W + R * W) * W * 2);
+    if (panel_ok(c)) A(&f->arena_panel, (size_t)c.n_blocks * c.n_layers * (3 * W + W + 2 * R * W) * W * 2);
     A((void **)&f->h, M * W * 4);
     A((void **)&f->p, M * 2 * D * 4);
     A(&f->a, M * W * ab);
@@ -746,6 +751,12 @@ int sjd_flow_load_weights(sjd_flow *f, const void *host_blob, size_t nbytes) {
             lw.p_qkv = prep_panel(lw.t_qkv, 3 * W);
             lw.p_o = prep_panel(lw.t_o, W);
             lw.p_fc1 = prep_panel(lw.t_fc1, R * W);
+            if (f->arena_panel) {                       // MLP output: [W, R W] transposed -> fragment order, k = R W
+                lw.p_fc2 = arp;
+                if (dt == SJD_DTYPE_BF16) launch_weights_to_frag32<bf16>((const bf16 *)lw.t_fc2, (bf16 *)arp, (int)W, (int)(R * W), 0);
+                else launch_weights_to_frag32<f16>((const f16 *)lw.t_fc2, (f16 *)arp, (int)W, (int)(R * W), 0);
+                arp += W * R * W * 2;
+            }
         }
         bw.lnf_g = p; p += W;
         bw.lnf_b = p; p += W;
@@ -938,24 +949,27 @@ int sjd_op_linear_h16(int dtype, int kernel, const void *a_dev, const void *wt_d
 
 int sjd_op_panel_linear_h16(int dtype, const void *a_dev, const float *ln_g_dev, const float *ln_b_dev,
                             const void *wt_dev, const float *bias_dev, float *resid_out_dev, void *c_dev, int M, int N,
-                            int epilogue, void *hip_stream) {
+                            int K, int epilogue, void *hip_stream) {
     if (!a_dev || !wt_dev || !bias_dev) return fail(SJD_EINVAL, "null device pointer");
     if (dtype != SJD_DTYPE_BF16 && dtype != SJD_DTYPE_F16) return fail(SJD_EINVAL, "dtype must be a 16-bit mode");
     if (epilogue < 0 || epilogue > 2) return fail(SJD_EINVAL, "epilogue must be 0..2");
     if (epilogue == 2 ? !resid_out_dev : (!c_dev || !ln_g_dev || !ln_b_dev)) return fail(SJD_EINVAL, "null device pointer");
-    if (!gemm_panel_applicable(M, N, 512, epilogue == 2 ? 4 : 2))
-        return fail(SJD_EINVAL, "the panel kernels need M >= 1, N a multiple of 256 and an output below 2 GiB");
-    if (epilogue == 2 && N > 512) return fail(SJD_EINVAL, "the residual variant covers N <= 512");
+    const bool stream = epilogue == 2 && K > 512;
+    if (stream ? !gemm_stream_applicable(M, N, K) : !gemm_panel_applicable(M, N, K, epilogue == 2 ? 4 : 2))
+        return fail(SJD_EINVAL, "need M >= 1, N a multiple of 256, K = 512 (or, residual variant, a multiple of 512) and operands below 2 GiB");
+    if (epilogue == 2 && K == 512 && N > 512) return fail(SJD_EINVAL, "the residual variant with K = 512 covers N <= 512");
     hipStream_t s = (hipStream_t)hip_stream;
     void *wf = nullptr;
-    HIP_TRY(hipMalloc(&wf, (size_t)N * 512 * 2));
+    HIP_TRY(hipMalloc(&wf, (size_t)N * K * 2));
     if (dtype == SJD_DTYPE_BF16) {
-        launch_weights_to_panel_frag<bf16>((const bf16 *)wt_dev, (bf16 *)wf, N, s);
-        if (epilogue == 2) launch_gemm_panel_resid<bf16>((const bf16 *)a_dev, (const bf16 *)wf, bias_dev, resid_out_dev, M, N, s);
+        launch_weights_to_frag32<bf16>((const bf16 *)wt_dev, (bf16 *)wf, N, K, s);
+        if (stream) launch_gemm_stream_resid<bf16>((const bf16 *)a_dev, (const bf16 *)wf, bias_dev, resid_out_dev, M, N, K, s);
+        else if (epilogue == 2) launch_gemm_panel_resid<bf16>((const bf16 *)a_dev, (const bf16 *)wf, bias_dev, resid_out_dev, M, N, s);
         else launch_ln_gemm_panel<bf16>((const float *)a_dev, ln_g_dev, ln_b_dev, (const bf16 *)wf, bias_dev, (bf16 *)c_dev, M, N, (Epi)epilogue, s);
     } else {
-        launch_weights_to_panel_frag<f16>((const f16 *)wt_dev, (f16 *)wf, N, s);
-        if (epilogue == 2) launch_gemm_panel_resid<f16>((const f16 *)a_dev, (const f16 *)wf, bias_dev, resid_out_dev, M, N, s);
+        launch_weights_to_frag32<f16>((const f16 *)wt_dev, (f16 *)wf, N, K, s);
+        if (stream) launch_gemm_stream_resid<f16>((const f16 *)a_dev, (const f16 *)wf, bias_dev, resid_out_dev, M, N, K, s);
+        else if (epilogue == 2) launch_gemm_panel_resid<f16>((const f16 *)a_dev, (const f16 *)wf, bias_dev, resid_out_dev, M, N, s);
         else launch_ln_gemm_panel<f16>((const float *)a_dev, ln_g_dev, ln_b_dev, (const f16 *)wf, bias_dev, (f16 *)c_dev, M, N, (Epi)epilogue, s);
     }
     const hipError_t e1 = hipStreamSynchronize(s), e2 = hipGetLastError();
