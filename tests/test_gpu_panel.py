@@ -150,6 +150,34 @@ def test_flow_gives_the_same_bits_on_both_projection_paths(torch_cuda, dtype_nam
     f.close()
 
 
+def test_headline_workload_takes_the_panel_kernels_and_gives_the_same_bits(torch_cuda):
+    """Configuration C2 at its full batch (16384 rows per pass: the launch configuration that bench.py
+    times): the automatic choice is the activation-stationary / streaming kernels, and a Jacobi block gives
+    the bits and pass counts of the tile kernels."""
+    import paper_2505_24791_amd as sjd
+    import workloads as wl
+    torch = torch_cuda
+    cfg = wl.CONFIGS["C2"]
+    f = sjd.Flow(cfg)
+    f.load_weights(wl.cached_weights(cfg))
+    z = torch.from_numpy(wl.make_latent(cfg)).cuda()
+    out = {}
+    for path in (1, 0):
+        f.set_projection_path(path)
+        f.profile_enable([sjd.PROF_GEMM, sjd.PROF_OTHER])
+        mu, alpha = f.conditioner(2, z)
+        x, iters, passes, _ = f.jacobi_inverse_block(1, z, sjd.JacobiOpts())
+        prof = f.profile_read(reset=True)
+        out[path] = (mu, alpha, x, iters.copy(), passes, prof)
+    for i in (0, 1, 2):
+        assert torch.equal(out[1][i], out[0][i]), i
+    assert np.array_equal(out[1][3], out[0][3]) and out[1][4] == out[0][4]
+    # the LayerNorm launches of the layers (family "other") are gone from the passes that took the panel kernels
+    assert out[0][5]["gemm"]["launches"] == out[1][5]["gemm"]["launches"]
+    assert out[0][5]["other"]["launches"] < out[1][5]["other"]["launches"]
+    f.close()
+
+
 def test_projection_path_is_validated(torch_cuda):
     import paper_2505_24791_amd as sjd
     import workloads as wl
