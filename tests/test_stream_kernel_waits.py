@@ -139,6 +139,27 @@ def test_compiled_kernel_keeps_in_flight_registers_untouched(kernel_isa):
             if m:
                 ring.update(range(int(m.group(1)), int(m.group(2)) + 1))
         assert len(ring) >= 64
+        # inside the loop, from a weight load to the first matrix instruction that takes its registers as
+        # second source, nothing else may touch them: a copy or a spill there would move data that has not
+        # arrived.  (Outside that span the allocator may use the registers for anything.)  The body is
+        # walked twice: the last loads of an iteration are consumed at the start of the next one.
+        in_flight = set()
+        for l in body + body:
+            if not re.match(r"\s+(v_|ds_|global_|buffer_|scratch_)", l):
+                continue
+            m = load.match(l)
+            if m:
+                dst = set(range(int(m.group(1)), int(m.group(2)) + 1))
+                assert not (_regs(l.split(",", 1)[1]) & in_flight), (name, l.strip())   # the address operands
+                assert not (dst & in_flight), (name, l.strip())
+                in_flight |= dst
+                continue
+            mm = re.match(r"\s+v_mfma\w+ a\[\d+:\d+\], (v\[\d+:\d+\]), (v\[\d+:\d+\]), a\[", l)
+            if mm:
+                assert not (_regs(mm.group(1)) & in_flight), (name, l.strip())
+                in_flight -= _regs(mm.group(2))
+                continue
+            assert not (_regs(l) & in_flight), (name, l.strip())
         # after the loop: nothing writes or reads a register that may still have a load in flight
         wait = next(i for i in range(end, len(lines)) if re.search(r"s_waitcnt vmcnt\(0\)", lines[i]))
         for l in lines[end:wait]:
