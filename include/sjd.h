@@ -206,6 +206,15 @@ SJD_API int sjd_op_panel_linear_h16(int dtype, const void *a_dev, const float *l
                                     const void *wt_dev, const float *bias_dev, float *resid_out_dev, void *c_dev, int M,
                                     int N, int K, int epilogue, void *hip_stream);
 
+/* Whole-sequence causal multi-head attention of the conditioner on its own (the attention inside s_k, g_k of
+ * eq. 5, evaluated for all positions at once as in the map F of Def. A.1), head size 64, in a 16-bit mode;
+ * exported so that the matrix-core attention kernel can be checked against the oracle at any token count.
+ * qkv_dev: DEVICE, [n_samples * T, 3 * H * 64] 16-bit row-major, columns [q | k | v], head h owning columns
+ * 64 h .. 64 h + 63 of each group.  o_dev: DEVICE, [n_samples * T, H * 64] 16-bit, position t attending
+ * positions 0..t with scale 1/8.  No T x T buffer is formed.  SJD_EINVAL for non-positive sizes or T > 4096. */
+SJD_API int sjd_op_attention_h16(int dtype, const void *qkv_dev, void *o_dev, int n_samples, int T, int H,
+                                 void *hip_stream);
+
 /* Which kernels the whole-sequence passes of a 16-bit flow use for their projections: 0 automatic (the
  * activation-stationary kernels for width 512 from 2048 rows on, the tile kernels otherwise), 1 tile
  * kernels with separate LayerNorm launches everywhere, 2 activation-stationary kernels for every row count

@@ -26,7 +26,7 @@ PROF_NAMES = ("gemm", "attention", "epilogue", "decode_gemm", "decode_attn", "ot
 EXPORTS = ("sjd_flow_create", "sjd_flow_load_weights", "sjd_jacobi_inverse_block", "sjd_sequential_inverse_block",
            "sjd_sample", "sjd_conditioner", "sjd_op_linear_h16", "sjd_jacobi_trace_block", "sjd_forward_block",
            "sjd_forward", "sjd_flow_set_mask_nearest", "sjd_flow_set_sequential_path", "sjd_flow_set_sequential_cus", "sjd_flow_set_projection_path",
-           "sjd_op_panel_linear_h16", "sjd_profile_enable", "sjd_profile_read", "sjd_flow_device_bytes",
+           "sjd_op_panel_linear_h16", "sjd_op_attention_h16", "sjd_profile_enable", "sjd_profile_read", "sjd_flow_device_bytes",
            "sjd_last_error", "sjd_flow_destroy")
 
 
@@ -84,6 +84,7 @@ def load_library() -> C.CDLL:
     lib.sjd_flow_set_sequential_cus.argtypes = [vp, C.c_int]
     lib.sjd_flow_set_mask_nearest.argtypes = [vp, C.c_int]
     lib.sjd_op_linear_h16.argtypes = [C.c_int, C.c_int, vp, vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, vp]
+    lib.sjd_op_attention_h16.argtypes = [C.c_int, vp, vp, C.c_int, C.c_int, C.c_int, vp]
     lib.sjd_profile_enable.argtypes = [vp, C.c_uint32]
     lib.sjd_profile_read.argtypes = [vp, C.POINTER(SjdProfile), C.c_int]
     lib.sjd_flow_device_bytes.argtypes = [vp]
@@ -167,6 +168,20 @@ def op_panel_linear_h16(a, wt, bias, M, N, epilogue, *, K=512, ln_g=None, ln_b=N
     _check(lib.sjd_op_panel_linear_h16(dtype, ptr(a), ptr(ln_g), ptr(ln_b), ptr(wt), ptr(bias), ptr(resid), ptr(c), M, N, K,
                                        epilogue, _stream_ptr()))
     return resid if epilogue == 2 else c
+
+
+def op_attention_h16(qkv, n_samples, T, H):
+    """``sjd_op_attention_h16`` on a torch tensor: qkv [n_samples*T, 3*H*64] float16 or bfloat16; returns o
+    [n_samples*T, H*64] of the same type."""
+    import torch
+    lib = load_library()
+    assert qkv.is_cuda and qkv.is_contiguous() and tuple(qkv.shape) == (n_samples * T, 3 * H * 64)
+    assert qkv.dtype in (torch.float16, torch.bfloat16)
+    dtype = DTYPE_F16 if qkv.dtype == torch.float16 else DTYPE_BF16
+    o = torch.empty((n_samples * T, H * 64), dtype=qkv.dtype, device=qkv.device)
+    _check(lib.sjd_op_attention_h16(dtype, C.c_void_p(qkv.data_ptr()), C.c_void_p(o.data_ptr()), n_samples, T, H,
+                                    _stream_ptr()))
+    return o
 
 
 class Flow:

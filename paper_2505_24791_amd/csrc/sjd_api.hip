@@ -776,6 +776,8 @@ int sjd_conditioner(sjd_flow *f, int block, const float *x_dev, float *mu_dev, f
     int rc = check_call(f, block, x_dev, mu_dev, batch);
     if (rc) return rc;
     if (!alpha_dev) return fail(SJD_EINVAL, "null device pointer");
+    if ((rc = check_call(f, block, x_dev, alpha_dev, batch))) return rc;
+    if ((rc = check_call(f, block, mu_dev, alpha_dev, batch))) return rc;
     hipStream_t s = (hipStream_t)hip_stream;
     HIP_TRY(hipSetDevice(f->device));
     conditioner_pass(f, block, x_dev, batch, nullptr, s);
@@ -976,6 +978,19 @@ int sjd_op_panel_linear_h16(int dtype, const void *a_dev, const float *ln_g_dev,
     (void)hipFree(wf);
     HIP_TRY(e1);
     HIP_TRY(e2);
+    return SJD_OK;
+}
+
+int sjd_op_attention_h16(int dtype, const void *qkv_dev, void *o_dev, int n_samples, int T, int H, void *hip_stream) {
+    if (!qkv_dev || !o_dev) return fail(SJD_EINVAL, "null device pointer");
+    if (dtype != SJD_DTYPE_BF16 && dtype != SJD_DTYPE_F16) return fail(SJD_EINVAL, "dtype must be a 16-bit mode");
+    if (n_samples < 1 || T < 1 || T > 4096 || H < 1 || H > 65535 || n_samples > 65535)
+        return fail(SJD_EINVAL, "need 1 <= n_samples, H <= 65535 and 1 <= T <= 4096");
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (dtype == SJD_DTYPE_BF16) launch_flash_attention_h16<bf16>((const bf16 *)qkv_dev, (bf16 *)o_dev, n_samples, T, H, s);
+    else launch_flash_attention_h16<f16>((const f16 *)qkv_dev, (f16 *)o_dev, n_samples, T, H, s);
+    HIP_TRY(hipStreamSynchronize(s));
+    HIP_TRY(hipGetLastError());
     return SJD_OK;
 }
 

@@ -1,0 +1,196 @@
+"""Configurations 3, 4 and 5 at their real token count, width, heads, layers and batch, through the C
+boundary, against the float32 CPU oracle.  Needs an MI355X.
+
+What is cut so that the oracle finishes in about a minute on the host cores: the number of flow
+blocks (the blocks of a flow are structurally alike; the cut flows keep block 0, which is inverted
+sequentially, and a Jacobi block on the reversed token order) and the number of samples the oracle
+recomputes (samples are independent: no operation of the method mixes them).  The GPU always runs
+the configuration's full batch, so the launches have the shapes `bench.py` times: the persistent
+sequential kernel with two row blocks at width 768, the 256x256 projection tiles at K = 3072 / 4096,
+flash attention over eight query tiles at T = 1024, per-step launches at T = 1024.
+
+Bounds: final samples within 2e-2 of the oracle, per-sample pass counts within one (16-bit rounding
+of the operands may move a stop by one pass); a sample whose last oracle delta lies within 1 % of
+tau is reported and left out of the count comparison.
+"""
+import numpy as np
+import pytest
+
+import workloads as wl
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(600)]
+
+TOL_16BIT = 2e-2
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return torch
+
+
+def _dev(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a, np.float32)).cuda()
+
+
+def _spread(batch, n):
+    return sorted({int(round(i * (batch - 1) / (n - 1))) for i in range(n)})
+
+
+def _compare_counts(name, iters, riters, deltas, tau):
+    """Per-sample pass counts within one; samples whose deciding oracle delta is within 1 % of tau are skipped."""
+    for j in range(riters.shape[0]):
+        for b in range(riters.shape[1]):
+            if deltas[j, b] > 0 and abs(deltas[j, b] - tau) <= 0.01 * tau:
+                print(f"{name}: block {j} sample {b} is knife-edge (oracle delta {deltas[j, b]:.4e}); count not compared")
+                continue
+            assert abs(int(iters[j, b]) - int(riters[j, b])) <= 1, (name, j, b, iters[j].tolist(), riters[j].tolist())
+
+
+LARGE = [
+    # name, blocks kept, oracle samples
+    ("C3", 3, 4),     # W = 768, 12 heads, batch 256 (two row blocks in the persistent kernel), z scaled by 0.9
+    ("C4", 2, 4),     # W = 1024, 16 heads, D = 48, batch 128
+    ("C5", 2, 4),     # T = 1024: per-step launches for block 0, eight query tiles in flash attention
+]
+
+
+@pytest.mark.parametrize("name,n_blocks,n_orc", LARGE, ids=[c[0] for c in LARGE])
+def test_large_config_sample_matches_oracle(torch_cuda, orc32, name, n_blocks, n_orc):
+    import paper_2505_24791_amd as sjd
+    torch = torch_cuda
+    full = wl.CONFIGS[name]
+    cfg = full.with_(n_blocks=n_blocks)
+    blob = wl.make_weights(cfg)                 # block j of the cut flow = block j of the configuration (seed per block)
+    z = wl.make_latent(cfg)                     # full batch, the configuration's noise temperature
+    assert abs(float(z.std()) - full.temperature) < 0.01
+    mask = ~1 & ((1 << n_blocks) - 1)
+    f = sjd.Flow(cfg)
+    f.load_weights(blob)
+    zd = _dev(torch, z)
+    x, stats, iters = f.sample(zd, mask, sjd.JacobiOpts(tau=cfg.tau))
+    xs = x.cpu().numpy()
+    print(f"{name}: GPU passes per block {stats['block_iters']}, ms per block {[round(v, 1) for v in stats['block_ms']]}",
+          flush=True)
+    picks = _spread(cfg.batch, n_orc)
+    rx, riters, rdel = orc32.sample(cfg, blob, z[picks], mask, cfg.tau)
+    err = float(np.abs(xs[picks] - rx).max())
+    print(f"{name}: max |err| on samples {picks}: {err:.3e}; oracle passes {riters.max(axis=1).tolist()}", flush=True)
+    assert err <= TOL_16BIT
+    _compare_counts(name, iters[:, picks], riters, rdel, cfg.tau)
+    # every sample of the batch: finite, block 0 took T-1 steps, Jacobi blocks between 2 passes and the cap
+    assert np.isfinite(xs).all()
+    assert (iters[0] == cfg.seq_len - 1).all()
+    assert (iters[1:] >= 2).all() and (iters[1:] <= cfg.seq_len).all()
+    # the forward map takes the samples back to the latent (Jacobi blocks stopped at tau: to a few tau)
+    zz, logdet = f.forward(x)
+    assert (zz - zd).abs().mean().item() <= 5 * cfg.tau
+    assert torch.isfinite(logdet).all()
+    # the same call again gives the same bits
+    x2, _, iters2 = f.sample(zd, mask, sjd.JacobiOpts(tau=cfg.tau))
+    assert torch.equal(x, x2) and np.array_equal(iters, iters2)
+    f.close()
+
+
+@pytest.mark.parametrize("name", ["C3", "C5"])
+def test_large_config_sequential_schedules_match_oracle(torch_cuda, orc32, name):
+    """Block 0 of the configuration by both schedules of the sequential inverse (per-step launches and
+    the persistent kernel) at the full batch, against eq. 5 in the oracle on a spread of samples."""
+    import paper_2505_24791_amd as sjd
+    torch = torch_cuda
+    cfg = wl.CONFIGS[name].with_(n_blocks=1)
+    blob = wl.make_weights(cfg)
+    z = wl.make_latent(cfg)
+    picks = _spread(cfg.batch, 4)
+    rx, _, _ = orc32.sample(cfg, blob, z[picks], 0, cfg.tau)
+    f = sjd.Flow(cfg)
+    f.load_weights(blob)
+    zd = _dev(torch, z)
+    outs = {}
+    for path in (1, 2):
+        f.set_sequential_path(path)
+        xs = f.sequential_inverse_block(0, zd)
+        outs[path] = xs
+        err = float(np.abs(xs.cpu().numpy()[picks] - rx).max())
+        print(f"{name} block 0, schedule {path}: max |err| {err:.3e}", flush=True)
+        assert err <= TOL_16BIT
+        assert torch.isfinite(xs).all()
+    # the two schedules sum in different orders: equal to rounding, not bitwise
+    assert (outs[1] - outs[2]).abs().max().item() <= TOL_16BIT
+    f.close()
+
+
+def test_config4_all_jacobi_matches_oracle(torch_cuda, orc32):
+    """Configuration 4's ablation: every block by Jacobi decoding (uniform Jacobi decoding), two
+    blocks of the flow, full batch on the GPU."""
+    import paper_2505_24791_amd as sjd
+    torch = torch_cuda
+    cfg = wl.CONFIGS["C4"].with_(n_blocks=2)
+    blob = wl.make_weights(cfg)
+    z = wl.make_latent(cfg)
+    f = sjd.Flow(cfg)
+    f.load_weights(blob)
+    x, stats, iters = f.sample(_dev(torch, z), 0b11, sjd.JacobiOpts(tau=cfg.tau))
+    picks = _spread(cfg.batch, 4)
+    rx, riters, rdel = orc32.sample(cfg, blob, z[picks], 0b11, cfg.tau)
+    err = float(np.abs(x.cpu().numpy()[picks] - rx).max())
+    print(f"C4 all-Jacobi: max |err| {err:.3e}; passes gpu {stats['block_iters']} oracle {riters.max(axis=1).tolist()}")
+    assert err <= TOL_16BIT
+    _compare_counts("C4 all-Jacobi", iters[:, picks], riters, rdel, cfg.tau)
+    f.close()
+
+
+# ------------------------------------------------------------------------------------------------
+# op level: the projection tiles at the long k of the MLP output, flash attention at T = 1024
+
+DEEP_SHAPES = [(600, 768, 3072), (520, 1024, 4096), (300, 260, 4096)]
+
+
+@pytest.mark.parametrize("kernel", [1, 2, 0], ids=["256x128x32", "256x256x64", "auto"])
+@pytest.mark.parametrize("dtype_name", ["float16", "bfloat16"])
+def test_projection_kernels_deep_k_match_oracle(torch_cuda, orc64, kernel, dtype_name):
+    import paper_2505_24791_amd as sjd
+    torch = torch_cuda
+    dtype = getattr(torch, dtype_name)
+    out_eps = 2.0 ** -11 if dtype_name == "float16" else 2.0 ** -8
+    for si, (M, N, K) in enumerate(DEEP_SHAPES):
+        g = np.random.default_rng(40 + si)
+        a = torch.from_numpy(g.standard_normal((M, K)).astype(np.float32)).to(dtype)
+        w = torch.from_numpy((g.standard_normal((K, N)) * 0.02).astype(np.float32)).to(dtype)
+        bias = torch.from_numpy(g.standard_normal(N).astype(np.float32) * 0.1)
+        wt = torch.zeros(((N + 255) // 256 * 256, K), dtype=dtype)
+        wt[:N] = w.T
+        ref = orc64.linear(a.float().numpy(), w.float().numpy(), bias.numpy())
+        scale = np.abs(ref).max()
+        ad, wd, bd = a.cuda(), wt.cuda(), bias.cuda()
+        c = sjd.op_linear_h16(ad, wd, bd, M, N, K, 0, kernel=kernel).float().cpu().numpy()
+        assert np.abs(c - ref).max() <= out_eps * scale + 1e-3, (kernel, M, N, K)
+        cg = sjd.op_linear_h16(ad, wd, bd, M, N, K, 1, kernel=kernel).float().cpu().numpy()
+        assert np.abs(cg - orc64.gelu(ref)).max() <= out_eps * scale + 1e-3, (kernel, M, N, K)
+        r0 = g.standard_normal((M, N)).astype(np.float32)
+        rd = torch.from_numpy(r0.copy()).cuda()
+        sjd.op_linear_h16(ad, wd, bd, M, N, K, 2, resid=rd, kernel=kernel)
+        assert np.abs(rd.cpu().numpy() - (r0 + ref)).max() <= 3e-4 * scale + 1e-4, (kernel, M, N, K)
+
+
+@pytest.mark.parametrize("dtype_name", ["float16", "bfloat16"])
+@pytest.mark.parametrize("T", [1024, 1000, 257])
+def test_flash_attention_long_sequence_matches_oracle(torch_cuda, orc64, dtype_name, T):
+    """Whole-sequence causal attention (head size 64) at the token count of configuration 5, a ragged
+    count just below it and one just past two query tiles, against the oracle's attention on the same
+    16-bit-rounded q, k, v."""
+    import paper_2505_24791_amd as sjd
+    torch = torch_cuda
+    dtype = getattr(torch, dtype_name)
+    n, H, dh = 2, 3, 64
+    W = H * dh
+    g = np.random.default_rng(T)
+    qkv = torch.from_numpy(g.standard_normal((n * T, 3 * W)).astype(np.float32)).to(dtype)
+    o = sjd.op_attention_h16(qkv.cuda(), n, T, H).float().cpu().numpy().reshape(n, T, W)
+    q32 = qkv.float().numpy().reshape(n, T, 3 * W)
+    out_eps = 2.0 ** -11 if dtype_name == "float16" else 2.0 ** -8
+    for i in range(n):
+        ref = orc64.causal_attention(q32[i, :, :W], q32[i, :, W:2 * W], q32[i, :, 2 * W:], H)
+        # probabilities are rounded to 16 bits before the second product: relative 2^-11 (2^-8) per term
+        assert np.abs(o[i] - ref).max() <= 4 * out_eps * np.abs(q32[i, :, 2 * W:]).max(), (T, dtype_name, i)

@@ -288,6 +288,37 @@ def test_sample_is_the_composition_of_block_calls(orc64):
         assert np.array_equal(cur, x[b])
 
 
+def test_sample_with_block_input_as_first_iterate_is_the_composition_of_block_calls(orc64):
+    """`sample(init=1)` starts every Jacobi block from that block's own input (Sec. 4.3's alternative
+    initialisation), in the order the block processes its tokens: on a flow with reversed blocks it must
+    equal the chain of single-block calls with x0 = the block's (canonical-order) input, pass counts
+    included - handing the block the un-flipped input as x0 would change the counts of the reversed
+    blocks.  The single-block call is itself pinned (flip conjugacy, Prop. 3.2 from any start)."""
+    cfg, blob, z = _flow(8, K=4, seed=3)
+    assert cfg.reverse_mask == 0b1010
+    mask = 0b1110
+    tau = 1e-3
+    x, iters, deltas = orc64.sample(cfg, blob, z, mask, tau, init=1)
+    x0, iters0, _ = orc64.sample(cfg, blob, z, mask, tau, init=0)
+    differs = False
+    for b in range(z.shape[0]):
+        cur = z[b]
+        for j in range(cfg.n_blocks):
+            if (mask >> j) & 1:
+                nxt, it, tr = orc64.jacobi_inverse_block(cfg, blob, j, cur, tau, x0=cur, want_trace=True)
+                assert iters[j, b] == it and deltas[j, b] == tr[-1], (j, b)
+                # the wrong reading (x0 in the other token order) is a different run
+                wrong, it_w, tr_w = orc64.jacobi_inverse_block(cfg, blob, j, cur, tau, x0=cur[::-1].copy(), want_trace=True)
+                differs |= (tr_w[0] != tr[0])
+                cur = nxt
+            else:
+                cur = orc64.sequential_inverse_block(cfg, blob, j, cur)
+        assert np.array_equal(cur, x[b])
+    assert differs
+    # both initialisations approximate the same sequential solution: results agree to a few tau
+    assert np.abs(x - x0).max() < 0.05 and not np.array_equal(iters, iters0)
+
+
 def test_samples_are_independent(orc64):
     cfg, blob, z = _flow(8)
     x, iters, _ = orc64.sample(cfg, blob, z, ~1, 1e-3)
