@@ -206,6 +206,17 @@ SJD_API int sjd_op_panel_linear_h16(int dtype, const void *a_dev, const float *l
                                     const void *wt_dev, const float *bias_dev, float *resid_out_dev, void *c_dev, int M,
                                     int N, int K, int epilogue, void *hip_stream);
 
+/* sjd_op_panel_linear_h16 for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same results (bit for bit);
+ * the temporary fragment-order copy of the weight lives in a device array of the library (4 MiB, present on
+ * every GPU the library runs on until the process ends) instead of a per-call allocation, so the weight is
+ * limited to 2 N K <= 4 MiB (SJD_EINVAL beyond, e.g. N = 1024 with K = 4096).  The call allocates and frees
+ * nothing.  Every call on a GPU shares that GPU's array: calls that overlap in time on one GPU race and must
+ * be serialised by the caller; calls in sequence need no clearing in between (each rewrites all it reads). */
+SJD_API int sjd_op_panel_linear_h16_noalloc(int dtype, const void *a_dev, const float *ln_g_dev, const float *ln_b_dev,
+                                            const void *wt_dev, const float *bias_dev, float *resid_out_dev, void *c_dev,
+                                            int M, int N, int K, int epilogue, void *hip_stream);
+
 /* Whole-sequence causal multi-head attention of the conditioner on its own (the attention inside s_k, g_k of
  * eq. 5, evaluated for all positions at once as in the map F of Def. A.1), head size 64, in a 16-bit mode;
  * exported so that the matrix-core attention kernel can be checked against the oracle at any token count.

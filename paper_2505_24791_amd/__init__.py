@@ -26,7 +26,7 @@ PROF_NAMES = ("gemm", "attention", "epilogue", "decode_gemm", "decode_attn", "ot
 EXPORTS = ("sjd_flow_create", "sjd_flow_load_weights", "sjd_jacobi_inverse_block", "sjd_sequential_inverse_block",
            "sjd_sample", "sjd_conditioner", "sjd_op_linear_h16", "sjd_jacobi_trace_block", "sjd_forward_block",
            "sjd_forward", "sjd_flow_set_mask_nearest", "sjd_flow_set_sequential_path", "sjd_flow_set_sequential_cus", "sjd_flow_set_projection_path",
-           "sjd_op_panel_linear_h16", "sjd_op_attention_h16", "sjd_profile_enable", "sjd_profile_read", "sjd_flow_device_bytes",
+           "sjd_op_panel_linear_h16", "sjd_op_panel_linear_h16_noalloc", "sjd_op_attention_h16", "sjd_profile_enable", "sjd_profile_read", "sjd_flow_device_bytes",
            "sjd_last_error", "sjd_flow_destroy")
 
 
@@ -149,7 +149,7 @@ def op_linear_h16(a, wt, bias, M, N, K, epilogue, *, resid=None, kernel=0):
     return resid if epilogue == 2 else c
 
 
-def op_panel_linear_h16(a, wt, bias, M, N, epilogue, *, K=512, ln_g=None, ln_b=None, resid=None):
+def op_panel_linear_h16(a, wt, bias, M, N, epilogue, *, K=512, ln_g=None, ln_b=None, resid=None, noalloc=False):
     """``sjd_op_panel_linear_h16`` on torch tensors.  epilogue 0 / 1 (K = 512): a [M,512] float32, ln_g / ln_b
     [512] float32, returns c [M,N] in wt's type; epilogue 2: a [M,K] 16-bit, updates ``resid`` in place."""
     import torch
@@ -165,8 +165,8 @@ def op_panel_linear_h16(a, wt, bias, M, N, epilogue, *, K=512, ln_g=None, ln_b=N
         assert a.dtype == torch.float32 and ln_g is not None and ln_b is not None
         c = torch.empty((M, N), dtype=wt.dtype, device=a.device)
     ptr = lambda t: C.c_void_p(t.data_ptr()) if t is not None else None
-    _check(lib.sjd_op_panel_linear_h16(dtype, ptr(a), ptr(ln_g), ptr(ln_b), ptr(wt), ptr(bias), ptr(resid), ptr(c), M, N, K,
-                                       epilogue, _stream_ptr()))
+    fn = lib.sjd_op_panel_linear_h16_noalloc if noalloc else lib.sjd_op_panel_linear_h16
+    _check(fn(dtype, ptr(a), ptr(ln_g), ptr(ln_b), ptr(wt), ptr(bias), ptr(resid), ptr(c), M, N, K, epilogue, _stream_ptr()))
     return resid if epilogue == 2 else c
 
 

@@ -9,6 +9,7 @@
 #include <string.h>
 
 #include <map>
+#include <mutex>
 #include <new>
 #include <tuple>
 #include <vector>
@@ -949,9 +950,10 @@ int sjd_op_linear_h16(int dtype, int kernel, const void *a_dev, const void *wt_d
     return SJD_OK;
 }
 
-int sjd_op_panel_linear_h16(int dtype, const void *a_dev, const float *ln_g_dev, const float *ln_b_dev,
-                            const void *wt_dev, const float *bias_dev, float *resid_out_dev, void *c_dev, int M, int N,
-                            int K, int epilogue, void *hip_stream) {
+namespace {
+
+int panel_linear_check(int dtype, const void *a_dev, const float *ln_g_dev, const float *ln_b_dev, const void *wt_dev,
+                       const float *bias_dev, float *resid_out_dev, void *c_dev, int M, int N, int K, int epilogue) {
     if (!a_dev || !wt_dev || !bias_dev) return fail(SJD_EINVAL, "null device pointer");
     if (dtype != SJD_DTYPE_BF16 && dtype != SJD_DTYPE_F16) return fail(SJD_EINVAL, "dtype must be a 16-bit mode");
     if (epilogue < 0 || epilogue > 2) return fail(SJD_EINVAL, "epilogue must be 0..2");
@@ -960,9 +962,15 @@ int sjd_op_panel_linear_h16(int dtype, const void *a_dev, const float *ln_g_dev,
     if (stream ? !gemm_stream_applicable(M, N, K) : !gemm_panel_applicable(M, N, K, epilogue == 2 ? 4 : 2))
         return fail(SJD_EINVAL, "need M >= 1, N a multiple of 256, K = 512 (or, residual variant, a multiple of 512) and operands below 2 GiB");
     if (epilogue == 2 && K == 512 && N > 512) return fail(SJD_EINVAL, "the residual variant with K = 512 covers N <= 512");
-    hipStream_t s = (hipStream_t)hip_stream;
-    void *wf = nullptr;
-    HIP_TRY(hipMalloc(&wf, (size_t)N * K * 2));
+    return SJD_OK;
+}
+
+// The op itself: reorders the weight into `wf` (device, 2 N K bytes, every byte written before it is read) and
+// launches the projection.  Asynchronous on s; allocates nothing.
+void panel_linear_run(int dtype, const void *a_dev, const float *ln_g_dev, const float *ln_b_dev, const void *wt_dev,
+                      const float *bias_dev, float *resid_out_dev, void *c_dev, int M, int N, int K, int epilogue,
+                      void *wf, hipStream_t s) {
+    const bool stream = epilogue == 2 && K > 512;
     if (dtype == SJD_DTYPE_BF16) {
         launch_weights_to_frag32<bf16>((const bf16 *)wt_dev, (bf16 *)wf, N, K, s);
         if (stream) launch_gemm_stream_resid<bf16>((const bf16 *)a_dev, (const bf16 *)wf, bias_dev, resid_out_dev, M, N, K, s);
@@ -974,10 +982,71 @@ int sjd_op_panel_linear_h16(int dtype, const void *a_dev, const float *ln_g_dev,
         else if (epilogue == 2) launch_gemm_panel_resid<f16>((const f16 *)a_dev, (const f16 *)wf, bias_dev, resid_out_dev, M, N, s);
         else launch_ln_gemm_panel<f16>((const float *)a_dev, ln_g_dev, ln_b_dev, (const f16 *)wf, bias_dev, (f16 *)c_dev, M, N, (Epi)epilogue, s);
     }
+}
+
+}  // namespace
+
+int sjd_op_panel_linear_h16(int dtype, const void *a_dev, const float *ln_g_dev, const float *ln_b_dev,
+                            const void *wt_dev, const float *bias_dev, float *resid_out_dev, void *c_dev, int M, int N,
+                            int K, int epilogue, void *hip_stream) {
+    int rc = panel_linear_check(dtype, a_dev, ln_g_dev, ln_b_dev, wt_dev, bias_dev, resid_out_dev, c_dev, M, N, K, epilogue);
+    if (rc) return rc;
+    hipStream_t s = (hipStream_t)hip_stream;
+    void *wf = nullptr;
+    HIP_TRY(hipMalloc(&wf, (size_t)N * K * 2));
+    panel_linear_run(dtype, a_dev, ln_g_dev, ln_b_dev, wt_dev, bias_dev, resid_out_dev, c_dev, M, N, K, epilogue, wf, s);
     const hipError_t e1 = hipStreamSynchronize(s), e2 = hipGetLastError();
     (void)hipFree(wf);
     HIP_TRY(e1);
     HIP_TRY(e2);
+    return SJD_OK;
+}
+
+// ---- the same op for callers that cannot allocate ------------------------------------------------
+// The fragment-order weight copy, which sjd_op_panel_linear_h16 allocates per call, lives in a file-scope
+// device array here.  In host code the array's name is only a stand-in: its device address is looked up
+// once per device (each GPU holds its own copy at its own address) and that pointer is what the kernels get.
+#define SJD_NOALLOC_SCRATCH_BYTES (4u << 20)
+static __device__ __align__(256) unsigned char scratch[SJD_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device; resolved on the first call per device.
+int scratch_address(void **out) {
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(SJD_EINVAL, "device index %d is outside 0..%d", dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return fail(SJD_EHIP, "hipGetSymbolAddress returned a null address for the scratch array");
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return SJD_OK;
+}
+}  // namespace
+
+int sjd_op_panel_linear_h16_noalloc(int dtype, const void *a_dev, const float *ln_g_dev, const float *ln_b_dev,
+                                    const void *wt_dev, const float *bias_dev, float *resid_out_dev, void *c_dev, int M,
+                                    int N, int K, int epilogue, void *hip_stream) {
+    int rc = panel_linear_check(dtype, a_dev, ln_g_dev, ln_b_dev, wt_dev, bias_dev, resid_out_dev, c_dev, M, N, K, epilogue);
+    if (rc) return rc;
+    if ((size_t)N * K * 2 > SJD_NOALLOC_SCRATCH_BYTES)
+        return fail(SJD_EINVAL, "the weight (%d x %d, %zu bytes in 16 bits) exceeds the %u-byte scratch of the non-allocating op",
+                    N, K, (size_t)N * K * 2, SJD_NOALLOC_SCRATCH_BYTES);
+    void *wf = nullptr;
+    if ((rc = scratch_address(&wf))) return rc;
+    hipStream_t s = (hipStream_t)hip_stream;
+    // every byte of the copy that the projection reads is rewritten by the reorder kernel in front of it:
+    // nothing of the previous call's contents is used, so nothing needs clearing
+    panel_linear_run(dtype, a_dev, ln_g_dev, ln_b_dev, wt_dev, bias_dev, resid_out_dev, c_dev, M, N, K, epilogue, wf, s);
+    HIP_TRY(hipStreamSynchronize(s));
+    HIP_TRY(hipGetLastError());
     return SJD_OK;
 }
 
