@@ -189,7 +189,8 @@ SJD_API int sjd_conditioner(sjd_flow *flow, int block, const float *x_dev, float
  * [N rounded up to a multiple of 256, K] 16-bit, K contiguous, padding rows zero.  bias_dev [N] float32.
  * epilogue 0: c_dev [M, N] 16-bit = A W + bias;  1: c_dev = GELU(A W + bias) (erf form);
  * 2: resid_out_dev [M, N] float32 += A W + bias (c_dev unused).  K must be a multiple of 64.
- * kernel: 0 chosen by shape, 1..3 a specific tile kernel.  dtype: SJD_DTYPE_BF16 or SJD_DTYPE_F16. */
+ * kernel: 0 chosen by shape, 1..3 a specific tile kernel, 4 the persistent eight-wave kernel (K a multiple of 128
+ * and N a multiple of 256; other shapes fall back to 0).  dtype: SJD_DTYPE_BF16 or SJD_DTYPE_F16. */
 SJD_API int sjd_op_linear_h16(int dtype, int kernel, const void *a_dev, const void *wt_dev, const float *bias_dev,
                               float *resid_out_dev, void *c_dev, int M, int N, int K, int epilogue, void *hip_stream);
 

@@ -139,10 +139,17 @@ void launch_gemm_f32(const float *A, const float *B, const float *bias, const fl
 // weight transposed, K contiguous, with at least round_up(N, 256) rows (zero filled).  K % 64 == 0.
 // OutT = HT (EPI_BIAS, EPI_BIAS_GELU) or float (EPI_BIAS, EPI_BIAS_RESIDUAL).
 // kernel: 0 = chosen by shape; 1 = 256x128x32 staged through registers; 2 = 256x256x64 LDS-direct;
-// 3 = 128x128x64 (the explicit choices exist so that each kernel can be checked on small shapes).
+// 3 = 128x128x64; 4 = the persistent eight-wave kernel of gemm_p8.hip where it applies (else as 0)
+// (the explicit choices exist so that each kernel can be checked on small shapes).
 template <typename HT, typename OutT>
 void launch_gemm_h16(const HT *A, const HT *Bt, const float *bias, const float *resid, OutT *C, int M, int N, int K,
                      Epi epi, hipStream_t s, int kernel = 0);
+
+// Persistent eight-wave projection (gemm_p8.hip): the same contract as launch_gemm_h16 (resid, when given, is C
+// itself: the float32 stream is updated in place) for K % 128 == 0 and N % 256 == 0; bit-identical to the tile kernels.
+bool gemm_p8_applicable(int M, int N, int K);
+template <typename HT, typename OutT>
+void launch_gemm_p8(const HT *A, const HT *Bt, const float *bias, OutT *C, int M, int N, int K, Epi epi, hipStream_t s);
 
 // Activation-stationary projections for K = 512 (gemm_panel.hip).  Wf: the weight in the fragment order of
 // the 32x32x16 instruction (launch_weights_to_panel_frag from the transposed [N, 512] copy; N % 256 == 0).

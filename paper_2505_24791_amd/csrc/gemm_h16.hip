@@ -420,6 +420,9 @@ static void pick_tile(const HT *A, const HT *Bt, const float *bias, const float 
     if (kernel == 1) return launch_tile<HT, 256, 128, 32, 2, OutT, EPI>(A, Bt, bias, resid, C, M, N, K, s);
     if (kernel == 2) return launch_dma<HT, OutT, EPI>(A, Bt, bias, resid, C, M, N, K, s);
     if (kernel == 3) return launch_tile<HT, 128, 128, 64, 1, OutT, EPI>(A, Bt, bias, resid, C, M, N, K, s);
+    // the persistent kernel updates the residual stream in place: resid, when used, must be C
+    const bool p8_ok = gemm_p8_applicable(M, N, K) && (EPI != EPI_BIAS_RESIDUAL || (const void *)resid == (const void *)C);
+    if (kernel == 4 && p8_ok) return launch_gemm_p8<HT, OutT>(A, Bt, bias, C, M, N, K, (Epi)EPI, s);
     const long t128 = (long)((M + 127) / 128) * ((N + 127) / 128);
     const long t256 = (long)((M + 255) / 256) * ((N + 255) / 256);
     const bool deep = K >= 3072 || (EPI == EPI_BIAS && K >= 768 && N >= 768);

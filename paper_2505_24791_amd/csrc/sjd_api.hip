@@ -933,7 +933,7 @@ int sjd_op_linear_h16(int dtype, int kernel, const void *a_dev, const void *wt_d
     if (!a_dev || !wt_dev || !bias_dev) return fail(SJD_EINVAL, "null device pointer");
     if (dtype != SJD_DTYPE_BF16 && dtype != SJD_DTYPE_F16) return fail(SJD_EINVAL, "dtype must be a 16-bit mode");
     if (M < 1 || N < 1 || K < 64 || K % 64) return fail(SJD_EINVAL, "need M, N >= 1 and K a positive multiple of 64");
-    if (kernel < 0 || kernel > 3) return fail(SJD_EINVAL, "kernel must be 0..3");
+    if (kernel < 0 || kernel > 4) return fail(SJD_EINVAL, "kernel must be 0..4");
     if (epilogue < 0 || epilogue > 2) return fail(SJD_EINVAL, "epilogue must be 0..2");
     if (epilogue == 2 ? !resid_out_dev : !c_dev) return fail(SJD_EINVAL, "null output pointer");
     hipStream_t s = (hipStream_t)hip_stream;
