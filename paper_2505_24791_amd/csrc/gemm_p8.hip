@@ -1,21 +1,24 @@
 // Persistent 16-bit MFMA projection, eight waves per workgroup: C[M,N] = epi(A[M,K] * Bt[N,K]^T + bias).
 //
-// The tile kernels of gemm_h16.hip run one wave per SIMD and one tile per workgroup: nothing covers a
-// wave's wait at the barrier that ends a k-tile, and every tile pays its first loads and its epilogue's
-// store drain in full, because the next workgroup cannot start on the CU before this one has gone
-// (128 KB of LDS each).  Here one workgroup per CU stays resident and walks over its tiles:
-//   * 256 x 256 output tile, k-tiles of 64, two 64 KB LDS stages filled by LDS-direct loads
-//     (whole 128-byte lines, no staging registers), same swizzle as gemm_h16_dma_kernel;
-//   * eight waves, two per SIMD, each owning 128 x 64 of the tile (128 accumulator registers):
-//     while one wave of a SIMD waits (barrier, LDS, the next k-tile's loads) the other issues matrix
-//     instructions;
-//   * the first k-tile of the NEXT tile is requested during the last k-tile of this one and has
-//     landed before the epilogue starts, so a tile begins with operands already in LDS;
+// The tile kernels of gemm_h16.hip run one tile per workgroup: every tile pays its first loads and the
+// drain of its epilogue's stores in full, because the next workgroup cannot start on the CU before this
+// one has gone (128 KB of LDS each).  Here one workgroup per CU stays resident and walks over its tiles:
+//   * 256 x 256 output tile; k-tiles of 32 in four 32 KB LDS stages filled by LDS-direct loads
+//     (no staging registers), requested three k-tiles ahead;
+//   * eight waves, two per SIMD, each owning 128 x 64 of the tile (128 accumulator registers);
+//   * the request stream runs on across tiles: the first three k-tiles of the NEXT tile are requested during
+//     the last ones of this tile and the first has landed before the epilogue starts, so a tile begins with
+//     operands already in LDS;
 //   * the epilogue parks accumulators in LDS of its own (32 KB beyond the stages), so the stages keep
 //     filling meanwhile, and its stores drain while the next tile multiplies.
 // k is walked in index order with the 32x32x16 instruction, an output row depends on its own row of A
 // only: results are bit-identical to the tile kernels and independent of the batch.
 // Covers K % 128 == 0 and N % 256 == 0 (every projection of the workloads but the head).
+// What bounds it (timing probes on M = 32768, N = 1024, K = 4096; 1.05 PFLOP/s as is): the same loop
+// without its global loads runs at 1.49 PFLOP/s, with loads that land in registers instead of LDS at 1.13,
+// without its LDS fragment reads (loads kept) at 1.00, without the barrier at 1.05; k-tiles of 64 in two
+// stages, one wave per SIMD, or padded row strides change nothing.  It is the operand traffic from L2
+// (64 KB per CU per 8.4 MFLOP, about 8 TB/s in all) that costs the difference, not latency, LDS or the barrier.
 #include "common.h"
 #include <atomic>
 
@@ -23,11 +26,12 @@ namespace sjd {
 
 namespace {
 
-constexpr int Q_BM = 256, Q_BN = 256, Q_BK = 64, Q_KSUB = Q_BK / 16;
-constexpr int Q_OPB = 32 * 1024;            // bytes of one operand in one stage: 256 rows x 128 B
-constexpr int Q_STB = 2 * Q_OPB;            // bytes per stage
-constexpr int Q_PARK = 2 * Q_STB;           // offset of the epilogue parking space: 8 waves x 16 rows x 64 floats
-constexpr int Q_LDS = Q_PARK + 8 * 4096;    // 160 KB
+constexpr int Q_BM = 256, Q_BN = 256;
+constexpr int D_BK = 32, D_KSUB = D_BK / 16, D_NS = 4;   // k-tile, k-steps per k-tile, LDS stages
+constexpr int D_OPB = 16 * 1024;            // bytes of one operand in one stage: 256 rows x 64 B
+constexpr int D_STB = 2 * D_OPB;            // bytes per stage
+constexpr int D_PARK = D_NS * D_STB;        // offset of the epilogue parking space: 8 waves x 16 rows x 64 floats
+constexpr int D_LDS = D_PARK + 8 * 4096;    // 160 KB
 constexpr int kOutside = 0x7FFFFFF0;        // a lane offset past any buffer range this kernel declares
 
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
@@ -59,69 +63,68 @@ __global__ __launch_bounds__(512) void gemm_h16_p8_kernel(const HT *__restrict__
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS bases stay in scalar registers
     const int l32 = lane & 31, g = lane >> 5;
     const int wm = wave >> 2, wn = wave & 3;                     // this wave's 128 x 64 part of the tile
-    const int KT = K / Q_BK;
+    const int KT = K / D_BK;
 
-    // Loads.  Per k-tile a wave brings the 8-row blocks 4 wave + i (i = 0..3) of A and of B, 1 KB each:
-    // lane 8 r + c delivers the 16-byte chunk that belongs in slot c of row r.  Row r of a 32-row fragment
-    // group keeps chunk c in slot c ^ swz(r), swz(r) = bits 1, 2 and 4 of r: a 16-byte LDS read of a wave
-    // is served in four passes of 16 lanes (lanes that agree in bits 3 and 5) over 64 banks, and the
-    // sixteen rows of a pass then fall on sixteen different 16-byte bank groups.
+    // Loads.  A stage holds a k-tile of 32: rows of 64 bytes (four 16-byte chunks), A then B, 16 KB each.  Per
+    // k-tile a wave brings the 16-row blocks 2 wave + i (i = 0, 1) of A and of B, 1 KB each: lane 4 r + c delivers
+    // the chunk that belongs in slot c of row r.  Row r of a 32-row fragment group keeps chunk c in slot
+    // c ^ swz(r), swz(r) = bits 2 and 4 of r: a 16-byte LDS read of a wave is served in four passes of 16 lanes
+    // (rows {0-7, 16-23} or {8-15, 24-31} of the group, one chunk) over 64 banks; with rows 64 bytes apart the
+    // bank group of a read is 4 (r mod 4) + slot, which this makes distinct over the sixteen rows of a pass.
     // Addresses are a wave-uniform 64-bit base (the tile's first row, advanced by the k-tile) plus a
     // per-lane 32-bit byte offset inside the tile: few registers, and no 32-bit overflow however large M is.
-    const int lr = lane >> 3;
-    const int lc0 = (lane & 7) ^ ((lr >> 1) & 3);                // chunk fetched for blocks with bit 4 of the row clear
+    const int lr = lane >> 2;                                    // row within the 16-row block
+    const int lc0 = (lane & 3) ^ ((lr >> 2) & 1);                // chunk fetched for blocks with bit 4 of the row clear
     const uint32_t row_bytes = (uint32_t)K * 2u;
-    struct Src { uint32_t a_off[4]; const char *a_base, *b_base; };
+    struct Src { uint32_t a_off[2]; const char *a_base, *b_base; };
     auto make_src = [&](int t) {
         Src s;
         const int tm = t / tiles_n, tn = t - tm * tiles_n;
         const int last = M - 1 - tm * Q_BM;                      // last valid row of this tile (tile-relative, >= 0)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            int row = (wave * 4 + i) * 8 + lr;
+        for (int i = 0; i < 2; ++i) {
+            int row = (wave * 2 + i) * 16 + lr;
             row = row < last ? row : last;                       // rows past the end: re-read the last row, never stored
-            s.a_off[i] = (uint32_t)row * row_bytes + (uint32_t)((lc0 ^ (((i >> 1) & 1) << 2)) * 16);
+            s.a_off[i] = (uint32_t)row * row_bytes + (uint32_t)((lc0 ^ (i << 1)) * 16);
         }
         s.a_base = reinterpret_cast<const char *>(A + (size_t)tm * Q_BM * K);
         s.b_base = reinterpret_cast<const char *>(Bt + (size_t)tn * Q_BN * K);   // Bt rows are padded to the tile
         return s;
     };
     uint32_t b_off[2];
-    b_off[0] = (uint32_t)(wave * 32 + lr) * row_bytes + (uint32_t)(lc0 * 16);
-    b_off[1] = (uint32_t)(wave * 32 + lr) * row_bytes + (uint32_t)((lc0 ^ 4) * 16);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+        b_off[i] = (uint32_t)((wave * 2 + i) * 16 + lr) * row_bytes + (uint32_t)((lc0 ^ (i << 1)) * 16);
     // An LDS-direct load: 64 lanes x 16 bytes from (wave-uniform base) + (per-lane 32-bit offset) to 1 KB of LDS
     // at the wave-uniform byte address lds_addr (through M0).  Written out so that the address stays split
-    // into a scalar base and a 32-bit lane offset (two registers per lane per load otherwise).
+    // into a scalar base and a 32-bit lane offset (two registers per lane per load otherwise).  M0 is set
+    // inside the statement and nothing else in this kernel reads it (no other LDS-direct access, no
+    // indexed register moves), so nothing of the compiler's is lost.
     auto dma = [&](const char *base, uint32_t off, uint32_t lds_addr) {
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                     :: "s"(lds_addr), "v"(off), "s"(base) : "memory", "m0");
+                     :: "s"(lds_addr), "v"(off), "s"(base) : "memory");
     };
     const uint32_t lds0 = (uint32_t)(uintptr_t)SJD_Q_LPTR(lds);
-    auto issue_load = [&](const Src &s, int kt, int stage, int q) {   // q = 0..7: this wave's eight blocks
-        const uint32_t st = lds0 + (uint32_t)(stage * Q_STB);
-        if (q < 4) {
-            dma(s.a_base + (size_t)kt * (Q_BK * 2), s.a_off[q], st + (uint32_t)((wave * 4 + q) * 1024));
-        } else {
-            const int i = q - 4;
-            dma(s.b_base + ((size_t)kt * (Q_BK * 2) + (size_t)i * 8 * row_bytes), b_off[(i >> 1) & 1],
-                st + (uint32_t)(Q_OPB + (wave * 4 + i) * 1024));
-        }
+    auto issue_load = [&](const Src &s, int kt, int stage, int q) {   // q = 0..3: this wave's four blocks
+        const uint32_t st = lds0 + (uint32_t)(stage * D_STB);
+        if (q < 2) dma(s.a_base + (size_t)kt * (D_BK * 2), s.a_off[q], st + (uint32_t)((wave * 2 + q) * 1024));
+        else dma(s.b_base + (size_t)kt * (D_BK * 2), b_off[q - 2], st + (uint32_t)(D_OPB + (wave * 2 + q - 2) * 1024));
     };
 
-    // Fragments: row l32 of a 32-row group, chunk 2 ks + g, found in slot (2 ks + g) ^ swz(l32); rows are 128 B
+    // Fragments: row l32 of a 32-row group, chunk 2 ks + g, found in slot (2 ks + g) ^ swz(l32); rows are 64 B
     // apart.  A fragments are refreshed in place right after their last use in a k-step, B fragments
     // (used by all four row groups) alternate between two sets.
-    const int swz = ((l32 >> 1) & 3) | (((l32 >> 4) & 1) << 2);
-    int fk[Q_KSUB];
+    const int swz = ((l32 >> 2) & 1) | (((l32 >> 4) & 1) << 1);
+    int fk[D_KSUB];
 #pragma unroll
-    for (int ks = 0; ks < Q_KSUB; ++ks) fk[ks] = l32 * 128 + (((2 * ks + g) ^ swz) << 4);
-    const int a_lds = wm * (128 * 128), b_lds = Q_OPB + wn * (64 * 128);
+    for (int ks = 0; ks < D_KSUB; ++ks) fk[ks] = l32 * 64 + (((2 * ks + g) ^ swz) << 4);
+    const int a_lds = wm * (128 * 64), b_lds = D_OPB + wn * (64 * 64);
     v8 fa[4], fb[2][2];
     auto read_a = [&](int stage, int ks, int i) {
-        fa[i] = *reinterpret_cast<const v8 *>(lds + (stage * Q_STB + a_lds + 32 * i * 128) + fk[ks]);
+        fa[i] = *reinterpret_cast<const v8 *>(lds + (stage * D_STB + a_lds + 32 * i * 64) + fk[ks]);
     };
     auto read_b = [&](int stage, int ks, int buf, int j) {
-        fb[buf][j] = *reinterpret_cast<const v8 *>(lds + (stage * Q_STB + b_lds + 32 * j * 128) + fk[ks]);
+        fb[buf][j] = *reinterpret_cast<const v8 *>(lds + (stage * D_STB + b_lds + 32 * j * 64) + fk[ks]);
     };
 
     f32x16 acc[4][2];
@@ -132,26 +135,27 @@ __global__ __launch_bounds__(512) void gemm_h16_p8_kernel(const HT *__restrict__
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // One k-tile: 32 matrix instructions of this wave, each a slot with its LDS reads and loads pinned.
-    // `next` / `next_kt`: the k-tile requested during this one, into the other stage (released by the
-    // barrier that ended the previous k-tile).  After the second slot of the last k-step: wait for this
-    // wave's own loads and LDS reads, then the barrier, after which the other stage holds the next
-    // k-tile and this stage may be refilled; the rest of the k-step reads the next k-tile's first fragments.
+    // One k-tile: 16 matrix instructions of this wave, each a slot with its LDS reads and loads pinned.
+    // `next` / `next_kt`: the k-tile requested during this one - three k-tiles ahead, into the stage that the
+    // previous k-tile used (released by the barrier that ended it).  After the second slot of the last k-step:
+    // wait until this wave's loads of the NEXT k-tile have landed (the eight younger ones, of the two k-tiles
+    // after it, may stay in flight: loads complete in order) and its LDS reads are done, then the barrier;
+    // the rest of the k-step reads the next k-tile's first fragments.
     auto ktile = [&](int stage, const Src &next, int next_kt) {
 #pragma unroll
-        for (int ks = 0; ks < Q_KSUB; ++ks) {
+        for (int ks = 0; ks < D_KSUB; ++ks) {
             const int b = ks & 1;
-            const bool last = ks + 1 == Q_KSUB;
-            const int rs = last ? stage ^ 1 : stage, rk = last ? 0 : ks + 1;   // where the next k-step's fragments are
+            const bool last = ks + 1 == D_KSUB;
+            const int rs = last ? (stage + 1) % D_NS : stage, rk = last ? 0 : ks + 1;   // where the next k-step's fragments are
 #pragma unroll
             for (int m = 0; m < 8; ++m) {
                 const int i = m >> 1, j = m & 1;
-                if (ks < 2 && j == 1) issue_load(next, next_kt, stage ^ 1, ks * 4 + i);
+                if (ks == 0 && j == 1) issue_load(next, next_kt, (stage + 3) % D_NS, i);
                 if (!last && m == 0) { read_b(rs, rk, b ^ 1, 0); read_b(rs, rk, b ^ 1, 1); }
                 acc[i][j] = Half16<HT>::mfma(fa[i], fb[b][j], acc[i][j]);
                 __builtin_amdgcn_sched_barrier(0);
                 if (last && m == 1) {
-                    __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
+                    __builtin_amdgcn_s_waitcnt(0x0078);   // vmcnt(8) lgkmcnt(0)
                     __builtin_amdgcn_s_barrier();
                     read_b(rs, rk, b ^ 1, 0);
                     read_b(rs, rk, b ^ 1, 1);
@@ -164,15 +168,17 @@ __global__ __launch_bounds__(512) void gemm_h16_p8_kernel(const HT *__restrict__
 
     Src cur = make_src(tile);
 #pragma unroll
-    for (int q = 0; q < 8; ++q) issue_load(cur, 0, 0, q);
-    __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0): the first k-tile has landed
+    for (int t = 0; t < 3; ++t)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) issue_load(cur, t, t, q);
+    __builtin_amdgcn_s_waitcnt(0x0F78);       // vmcnt(8): the first k-tile has landed
     __builtin_amdgcn_s_barrier();
 #pragma unroll
     for (int i = 0; i < 4; ++i) read_a(0, 0, i);
     read_b(0, 0, 0, 0);
     read_b(0, 0, 0, 1);
 
-    float *ep = reinterpret_cast<float *>(lds + Q_PARK) + wave * 1024;
+    float *ep = reinterpret_cast<float *>(lds + D_PARK) + wave * 1024;
     const int rl = lane >> 4, cl = (lane & 15) * 4;
 
     while (true) {
@@ -182,19 +188,22 @@ __global__ __launch_bounds__(512) void gemm_h16_p8_kernel(const HT *__restrict__
         // no next tile: request this tile's first k-tile again (in bounds, never used)
         const Src nxt = make_src(tile_next >= 0 ? tile_next : tile);
 
-        // two k-tiles per trip (stage 0, stage 1); the second one of the last trip requests the next tile's first
-        // k-tile - by selecting the source, not by branching: one straight-line loop body
-        for (int kt = 0; kt + 1 < KT; kt += 2) {
-            ktile(0, cur, kt + 1);
-            const bool wrap = kt + 2 >= KT;
+        // four k-tiles per trip (stages 0..3); in the last trip the requests run over into the next tile's first
+        // three k-tiles - by selecting the source, not by branching: one straight-line loop body
+        for (int kt = 0; kt < KT; kt += 4) {
+            ktile(0, cur, kt + 3);
+            const bool wrap = kt + 4 >= KT;
             Src sel;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) sel.a_off[i] = wrap ? nxt.a_off[i] : cur.a_off[i];
+            for (int i = 0; i < 2; ++i) sel.a_off[i] = wrap ? nxt.a_off[i] : cur.a_off[i];
             sel.a_base = wrap ? nxt.a_base : cur.a_base;
             sel.b_base = wrap ? nxt.b_base : cur.b_base;
-            ktile(1, sel, wrap ? 0 : kt + 2);
+            const int k0 = wrap ? 0 : kt + 4;
+            ktile(1, sel, k0);
+            ktile(2, sel, k0 + 1);
+            ktile(3, sel, k0 + 2);
         }
-        // here: stage 0 holds the next tile's first k-tile, fa / fb[0] its first fragments
+        // here: stage 0 holds the next tile's first k-tile (two more are on their way), fa / fb[0] its first fragments
 
         // ---- epilogue.  In the accumulators a lane owns one column and sixteen rows of a 32x32 block
         // (register v: row 8 (v / 4) + 4 g + v % 4).  Sixteen rows x 64 columns at a time go through the
@@ -272,7 +281,7 @@ __global__ __launch_bounds__(512) void gemm_h16_p8_kernel(const HT *__restrict__
         tile = tile_next;
         cur = nxt;
     }
-    __builtin_amdgcn_s_waitcnt(0x0F70);       // the loads of the unused last request have landed before the LDS goes away
+    __builtin_amdgcn_s_waitcnt(0x0F70);       // the loads of the unused last requests have landed before the LDS goes away
 }
 
 int p8_cus() {
@@ -304,10 +313,10 @@ static void launch_p8_one(const HT *A, const HT *Bt, const float *bias, OutT *C,
     auto kern = gemm_h16_p8_kernel<HT, OutT, EPI>;
     static std::atomic<bool> attr_set{false};   // callers may come from several host threads
     if (!attr_set.load(std::memory_order_acquire)) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, Q_LDS);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, D_LDS);
         attr_set.store(true, std::memory_order_release);
     }
-    hipLaunchKernelGGL(kern, dim3(8 * slots), dim3(512), Q_LDS, s, A, Bt, bias, C, M, N, K, tiles_n, n_tiles, per_xcd);
+    hipLaunchKernelGGL(kern, dim3(8 * slots), dim3(512), D_LDS, s, A, Bt, bias, C, M, N, K, tiles_n, n_tiles, per_xcd);
 }
 
 template <typename HT, typename OutT>

@@ -30,8 +30,9 @@ def _operands(torch, M, N, K, dtype, seed):
     return a, w, w.T.contiguous(), bias
 
 
+@pytest.mark.parametrize("kernel", [4])
 @pytest.mark.parametrize("dtype_name", ["float16", "bfloat16"])
-def test_persistent_kernel_matches_oracle_and_tile_kernel(torch_cuda, orc64, dtype_name):
+def test_persistent_kernel_matches_oracle_and_tile_kernel(torch_cuda, orc64, dtype_name, kernel):
     import paper_2505_24791_amd as sjd
     torch = torch_cuda
     dtype = getattr(torch, dtype_name)
@@ -44,25 +45,26 @@ def test_persistent_kernel_matches_oracle_and_tile_kernel(torch_cuda, orc64, dty
         ref = orc64.linear(a.float().numpy()[rows], w.float().numpy(), bias.numpy())
         scale = np.abs(ref).max()
         for epi in (0, 1):
-            c = sjd.op_linear_h16(ad, wd, bd, M, N, K, epi, kernel=4)
+            c = sjd.op_linear_h16(ad, wd, bd, M, N, K, epi, kernel=kernel)
             want = ref if epi == 0 else orc64.gelu(ref)
             assert np.abs(c.float().cpu().numpy()[rows] - want).max() <= out_eps * scale + 1e-3, (dtype_name, M, N, K, epi)
             assert torch.equal(c, sjd.op_linear_h16(ad, wd, bd, M, N, K, epi, kernel=3)), (dtype_name, M, N, K, epi)
         r0 = np.random.default_rng(99).standard_normal((M, N)).astype(np.float32)
         rd = torch.from_numpy(r0.copy()).cuda()
-        sjd.op_linear_h16(ad, wd, bd, M, N, K, 2, resid=rd, kernel=4)
+        sjd.op_linear_h16(ad, wd, bd, M, N, K, 2, resid=rd, kernel=kernel)
         assert np.abs(rd.cpu().numpy()[rows] - (r0[rows] + ref)).max() <= 3e-4 * scale + 1e-4, (dtype_name, M, N, K)
         rt = torch.from_numpy(r0.copy()).cuda()
         sjd.op_linear_h16(ad, wd, bd, M, N, K, 2, resid=rt, kernel=3)
         assert torch.equal(rd, rt), (dtype_name, M, N, K)
 
 
-def test_persistent_kernel_rows_do_not_depend_on_their_neighbours(torch_cuda):
+@pytest.mark.parametrize("kernel", [4])
+def test_persistent_kernel_rows_do_not_depend_on_their_neighbours(torch_cuda, kernel):
     import paper_2505_24791_amd as sjd
     torch = torch_cuda
     M, N, K = 2048, 512, 256
     a, w, wt, bias = _operands(torch, M, N, K, torch.float16, seed=5)
     ad, wd, bd = a.cuda(), wt.cuda(), bias.cuda()
-    full = sjd.op_linear_h16(ad, wd, bd, M, N, K, 0, kernel=4)
-    part = sjd.op_linear_h16(ad[300:556].contiguous(), wd, bd, 256, N, K, 0, kernel=4)
+    full = sjd.op_linear_h16(ad, wd, bd, M, N, K, 0, kernel=kernel)
+    part = sjd.op_linear_h16(ad[300:556].contiguous(), wd, bd, 256, N, K, 0, kernel=kernel)
     assert torch.equal(full[300:556], part)
