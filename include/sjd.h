@@ -93,14 +93,18 @@ typedef struct {
 } sjd_stats;
 
 /* Timing of kernel families inside the library (for roofline reports).  Off by default. */
-#define SJD_PROF_GEMM 0        /* all dense projections of whole-sequence passes */
+#define SJD_PROF_GEMM 0        /* whole-sequence passes: the fused q/k/v projection */
 #define SJD_PROF_ATTENTION 1   /* whole-sequence causal attention */
 #define SJD_PROF_EPILOGUE 2    /* fused affine update / difference reduction / convergence */
 #define SJD_PROF_DECODE_GEMM 3 /* projections of single-token steps */
 #define SJD_PROF_DECODE_ATTN 4 /* KV-cached single-token attention */
 #define SJD_PROF_OTHER 5       /* embedding, LayerNorm, ... */
 #define SJD_PROF_DECODE_FUSED 6 /* the sequential inverse of a whole block as one persistent kernel */
-#define SJD_PROF_FAMILIES 7
+#define SJD_PROF_GEMM_O 7      /* whole-sequence passes: attention-output projection (residual epilogue) */
+#define SJD_PROF_GEMM_FC1 8    /* whole-sequence passes: MLP input projection (GELU epilogue) */
+#define SJD_PROF_GEMM_FC2 9    /* whole-sequence passes: MLP output projection (residual epilogue) */
+#define SJD_PROF_GEMM_HEAD 10  /* whole-sequence passes: the [mu | alpha] head */
+#define SJD_PROF_FAMILIES 11
 typedef struct {
     double ms[SJD_PROF_FAMILIES];       /* summed device time per family since the last reset */
     int64_t launches[SJD_PROF_FAMILIES];

@@ -407,18 +407,40 @@ __global__ __launch_bounds__(256) void decode_attention_h16_kernel(const HT *__r
         for (int e = 0; e < 8; ++e) qf[e] = (float)q8[e] * 0.125f;  // 1/sqrt(64)
     }
     const int n = t + 1;
+    // Keys and values are walked four rows per thread at a time with all four loads issued before the first
+    // is used: with one load in flight per thread a workgroup has 4 KB on its way, and the step is spent
+    // waiting for memory latency thirty times over; rows past the end re-read the fresh row and are ignored.
+    // Each thread still accumulates its rows in index order.
+    constexpr int U = 4;
     float mx = -INFINITY;
-    for (int s = sg; s < n; s += 32) {
-        const HT *kr = s < t ? kc + (size_t)s * W + dc * 8 : kfresh;
-        const v8 k8 = *reinterpret_cast<const v8 *>(kr);
-        float d = 0.f;
+    for (int s0 = sg; s0 < n; s0 += 32 * U) {
+        v8 k8[U];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) d = fmaf(qf[e], (float)k8[e], d);
-        d += __shfl_xor(d, 1, 64);
-        d += __shfl_xor(d, 2, 64);
-        d += __shfl_xor(d, 4, 64);
-        if (dc == 0) sc[s] = d;
-        mx = fmaxf(mx, d);
+        for (int u = 0; u < U; ++u) {
+            const int s = s0 + 32 * u;
+            k8[u] = *reinterpret_cast<const v8 *>(s < t ? kc + (size_t)s * W + dc * 8 : kfresh);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int s = s0 + 32 * u;
+            if (s < n) {                       // the eight lanes of a key group agree on s
+                float d = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) d = fmaf(qf[e], (float)k8[u][e], d);
+                d += __shfl_xor(d, 1, 64);
+                d += __shfl_xor(d, 2, 64);
+                d += __shfl_xor(d, 4, 64);
+                if (dc == 0) sc[s] = d;
+                mx = fmaxf(mx, d);
+            }
+        }
+    }
+    // the first values are requested before the maximum is known
+    v8 vq[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int s = sg + 32 * u;
+        vq[u] = *reinterpret_cast<const v8 *>(s < t ? vc + (size_t)s * W + dc * 8 : vfresh);
     }
     mx = wave_max(mx);
     if (lane == 0) wmax[wave] = mx;
@@ -428,13 +450,25 @@ __global__ __launch_bounds__(256) void decode_attention_h16_kernel(const HT *__r
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = 0.f;
     float psum = 0.f;
-    for (int s = sg; s < n; s += 32) {
-        const float p = expf(sc[s] - mx);
-        const HT *vr = s < t ? vc + (size_t)s * W + dc * 8 : vfresh;
-        const v8 v8v = *reinterpret_cast<const v8 *>(vr);
+    for (int s0 = sg; s0 < n; s0 += 32 * U) {
+        v8 vn[U];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] = fmaf(p, (float)v8v[e], acc[e]);
-        psum += p;
+        for (int u = 0; u < U; ++u) {          // the next four rows, while these four are used
+            const int s = s0 + 32 * (U + u);
+            vn[u] = *reinterpret_cast<const v8 *>(s < t ? vc + (size_t)s * W + dc * 8 : vfresh);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int s = s0 + 32 * u;
+            if (s < n) {
+                const float p = expf(sc[s] - mx);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[e] = fmaf(p, (float)vq[u][e], acc[e]);
+                psum += p;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) vq[u] = vn[u];
     }
     // combine the 8 key groups of this wave (lanes differing in bits 3..5), then the 4 waves
 #pragma unroll
@@ -502,7 +536,17 @@ __global__ __launch_bounds__(256) void decode_advance_kernel(const float *__rest
         __syncthreads();
         for (int w = threadIdx.x; w < W; w += 256) {
             float acc = b_in[w];
-            for (int d = 0; d < D; ++d) acc = fmaf(xs[d], w_in[(size_t)d * W + w], acc);
+            // eight rows of the embedding matrix are requested before the first is used (one dependent round
+            // trip per row otherwise); the sum still runs over d in index order
+            int d = 0;
+            for (; d + 8 <= D; d += 8) {
+                float wv[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) wv[u] = w_in[(size_t)(d + u) * W + w];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) acc = fmaf(xs[d + u], wv[u], acc);
+            }
+            for (; d < D; ++d) acc = fmaf(xs[d], w_in[(size_t)d * W + w], acc);
             const size_t ho = frag ? frag_off(b, w, W / 32) : (size_t)b * W + w;
             h[ho] = acc + pos[(size_t)l * W + w];
         }
