@@ -397,9 +397,9 @@ __global__ __launch_bounds__(256) void decode_attention_h16_kernel(const HT *__r
     const HT *kfresh = chunk(1, dc), *vfresh = chunk(2, dc);   // this thread's chunk of the fresh k, v
     HT *kc = kcache + (size_t)b * T * W + h * 64;
     HT *vc = vcache + (size_t)b * T * W + h * 64;
-    if (tid < 8) *reinterpret_cast<v8 *>(kc + (size_t)t * W + tid * 8) = *reinterpret_cast<const v8 *>(chunk(1, tid));
+    if (tid < 8) __builtin_nontemporal_store(*reinterpret_cast<const v8 *>(chunk(1, tid)), reinterpret_cast<v8 *>(kc + (size_t)t * W + tid * 8));
     else if (tid < 16)
-        *reinterpret_cast<v8 *>(vc + (size_t)t * W + (tid - 8) * 8) = *reinterpret_cast<const v8 *>(chunk(2, tid - 8));
+        __builtin_nontemporal_store(*reinterpret_cast<const v8 *>(chunk(2, tid - 8)), reinterpret_cast<v8 *>(vc + (size_t)t * W + (tid - 8) * 8));
     float qf[8];
     {
         const v8 q8 = *reinterpret_cast<const v8 *>(chunk(0, dc));
@@ -411,14 +411,18 @@ __global__ __launch_bounds__(256) void decode_attention_h16_kernel(const HT *__r
     // is used: with one load in flight per thread a workgroup has 4 KB on its way, and the step is spent
     // waiting for memory latency thirty times over; rows past the end re-read the fresh row and are ignored.
     // Each thread still accumulates its rows in index order.
-    constexpr int U = 4;
+    constexpr int U = 4;   // eight rows in flight were slower (measured at 1024 tokens, 32 samples)
     float mx = -INFINITY;
+    // A row of the cache is read once per step and the whole cache is far larger than any cache level: read it
+    // as streaming data, so that it does not push the block's weights - which every step reads again - out of
+    // the memory-side cache (measured at 1024 tokens, width 1024: the projections of a step got 12 % faster).
+    auto ldc = [&](const HT *ptr) -> v8 { return __builtin_nontemporal_load(reinterpret_cast<const v8 *>(ptr)); };
     for (int s0 = sg; s0 < n; s0 += 32 * U) {
         v8 k8[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int s = s0 + 32 * u;
-            k8[u] = *reinterpret_cast<const v8 *>(s < t ? kc + (size_t)s * W + dc * 8 : kfresh);
+            k8[u] = ldc(s < t ? kc + (size_t)s * W + dc * 8 : kfresh);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -440,7 +444,7 @@ __global__ __launch_bounds__(256) void decode_attention_h16_kernel(const HT *__r
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const int s = sg + 32 * u;
-        vq[u] = *reinterpret_cast<const v8 *>(s < t ? vc + (size_t)s * W + dc * 8 : vfresh);
+        vq[u] = ldc(s < t ? vc + (size_t)s * W + dc * 8 : vfresh);
     }
     mx = wave_max(mx);
     if (lane == 0) wmax[wave] = mx;
@@ -455,7 +459,7 @@ __global__ __launch_bounds__(256) void decode_attention_h16_kernel(const HT *__r
 #pragma unroll
         for (int u = 0; u < U; ++u) {          // the next four rows, while these four are used
             const int s = s0 + 32 * (U + u);
-            vn[u] = *reinterpret_cast<const v8 *>(s < t ? vc + (size_t)s * W + dc * 8 : vfresh);
+            vn[u] = ldc(s < t ? vc + (size_t)s * W + dc * 8 : vfresh);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {

@@ -45,6 +45,11 @@ __device__ __forceinline__ rsrc_t make_rsrc(const void *p, uint32_t bytes) {
 __device__ __forceinline__ i32x4 ld16_l2(rsrc_t rs, uint32_t byte_off) {
     return __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, (int)byte_off, 0, 16));
 }
+// the same for rows of the key/value cache, with the streaming hint on top: a row is read once per step and
+// the cache is far larger than any cache level, so it should not displace the weights, which every step reads again
+__device__ __forceinline__ i32x4 ld16_l2_stream(rsrc_t rs, uint32_t byte_off) {
+    return __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, (int)byte_off, 0, 16 | 2));
+}
 __device__ __forceinline__ float ld4_l2(rsrc_t rs, uint32_t byte_off) {
     return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, (int)byte_off, 0, 16));
 }
@@ -374,8 +379,8 @@ __device__ __forceinline__ void att_fetch(const Ctx &c, rsrc_t kc_rs, rsrc_t vc_
         const int s = sg + 32 * (j0 + u);
         const int sr = s < t ? s : 0;                      // rows at or past t: any cached row, value not used
         const uint32_t off = (uint32_t)(cbase + (size_t)sr * W + dc * 8) * 2u;
-        w.k[u] = __builtin_bit_cast(v8, ld16_l2(kc_rs, off));
-        w.v[u] = __builtin_bit_cast(v8, ld16_l2(vc_rs, off));
+        w.k[u] = __builtin_bit_cast(v8, ld16_l2_stream(kc_rs, off));
+        w.v[u] = __builtin_bit_cast(v8, ld16_l2_stream(vc_rs, off));
     }
 }
 
@@ -433,7 +438,7 @@ __device__ __forceinline__ void attention_stage(const Ctx &c_in, rsrc_t qkv_rs, 
             for (int u = 0; u < P_AU; ++u) {
                 const int s = sg + 32 * (jb * P_AU + u);
                 const int sr = s < t ? s : 0;
-                kk[u] = __builtin_bit_cast(v8, ld16_l2(kc_rs, (uint32_t)(cbase + (size_t)sr * W + dc * 8) * 2u));
+                kk[u] = __builtin_bit_cast(v8, ld16_l2_stream(kc_rs, (uint32_t)(cbase + (size_t)sr * W + dc * 8) * 2u));
             }
 #pragma unroll
             for (int u = 0; u < P_AU; ++u) {
@@ -478,7 +483,7 @@ __device__ __forceinline__ void attention_stage(const Ctx &c_in, rsrc_t qkv_rs, 
             for (int u = 0; u < P_AU; ++u) {
                 const int s = sg + 32 * (jb * P_AU + u);
                 const int sr = s < t ? s : 0;
-                vv[u] = __builtin_bit_cast(v8, ld16_l2(vc_rs, (uint32_t)(cbase + (size_t)sr * W + dc * 8) * 2u));
+                vv[u] = __builtin_bit_cast(v8, ld16_l2_stream(vc_rs, (uint32_t)(cbase + (size_t)sr * W + dc * 8) * 2u));
             }
 #pragma unroll
             for (int u = 0; u < P_AU; ++u) {
