@@ -549,15 +549,17 @@ __global__ __launch_bounds__(P_THREADS) void seq_persistent_kernel(SeqArgs a) {
     if (c.tid == 0) {
         const int xcc = __builtin_amdgcn_s_getreg(20 | (3 << 11)) & 7;  // HW_REG_XCC_ID, bits 3:0
         const int slot = atomicAdd(&a.sync[xcc], 1);
-        atomicAdd(&a.sync[8], 1);
+        // the arrival is a release and the poll an acquire (device scope, once per launch): a member that sees
+        // every arrival also sees every member count, so all members of a group compute the same group size
+        __hip_atomic_fetch_add(&a.sync[8], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
         int it = 0, ok = 1;
-        while (__hip_atomic_load(&a.sync[8], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < (int)gridDim.x) {
+        while (__hip_atomic_load(&a.sync[8], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < (int)gridDim.x) {
             if (++it > a.spin_max) { ok = 0; break; }
             __builtin_amdgcn_s_sleep(2);
         }
         int n = 0, groups = 0, gidx = 0;
         for (int g = 0; g < 8; ++g) {
-            const int m = __hip_atomic_load(&a.sync[g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int m = __hip_atomic_load(&a.sync[g], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
             if (m > 0) { if (g < xcc) ++gidx; ++groups; }
             if (g == xcc) n = m;
         }

@@ -418,7 +418,8 @@ template <typename HT, typename OutT, int EPI>
 static void pick_tile(const HT *A, const HT *Bt, const float *bias, const float *resid, OutT *C, int M, int N, int K,
                       int kernel, hipStream_t s) {
     if (kernel == 1) return launch_tile<HT, 256, 128, 32, 2, OutT, EPI>(A, Bt, bias, resid, C, M, N, K, s);
-    if (kernel == 2) return launch_dma<HT, OutT, EPI>(A, Bt, bias, resid, C, M, N, K, s);
+    if (kernel == 2 && (long long)M * K < (1ll << 32) && (long long)(N + 256) * K < (1ll << 32))
+        return launch_dma<HT, OutT, EPI>(A, Bt, bias, resid, C, M, N, K, s);
     if (kernel == 3) return launch_tile<HT, 128, 128, 64, 1, OutT, EPI>(A, Bt, bias, resid, C, M, N, K, s);
     // the persistent kernel updates the residual stream in place: resid, when used, must be C
     const bool p8_ok = gemm_p8_applicable(M, N, K) && (EPI != EPI_BIAS_RESIDUAL || (const void *)resid == (const void *)C);
@@ -429,7 +430,9 @@ static void pick_tile(const HT *A, const HT *Bt, const float *bias, const float 
     // K <= 1024, even at K = 4096; with fewer tiles the finer grain of the kernels below wins)
     if (p8_ok && t256 >= 256) return launch_gemm_p8<HT, OutT>(A, Bt, bias, C, M, N, K, (Epi)EPI, s);
     const bool deep = K >= 3072 || (EPI == EPI_BIAS && K >= 768 && N >= 768);
-    if (deep && M >= 256 && N >= 256 && t256 >= 256) launch_dma<HT, OutT, EPI>(A, Bt, bias, resid, C, M, N, K, s);
+    // the LDS-direct kernel forms element offsets of A in 32 bits
+    const bool dma_ok = (long long)M * K < (1ll << 32) && (long long)(N + 256) * K < (1ll << 32);
+    if (deep && dma_ok && M >= 256 && N >= 256 && t256 >= 256) launch_dma<HT, OutT, EPI>(A, Bt, bias, resid, C, M, N, K, s);
     // measured: below ~3500 tiles of 128x128 the smaller tile wins (finer tail, shorter prologue per tile)
     else if (N >= 128 && M >= 256 && t128 >= 3584) launch_tile<HT, 256, 128, 32, 2, OutT, EPI>(A, Bt, bias, resid, C, M, N, K, s);
     else launch_tile<HT, 128, 128, 64, 1, OutT, EPI>(A, Bt, bias, resid, C, M, N, K, s);

@@ -45,19 +45,29 @@ template <typename V8, typename HT>
 __device__ __forceinline__ void load_untracked(V8 &dst, const HT *p) {
     asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(p) : "memory");
 }
-// s_waitcnt immediate for "at most n vector-memory operations outstanding", other counters untouched
-constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
-// wait until at most n (14..31) vector-memory operations are outstanding; n folds to a constant once the
-// loops around the call are unrolled (the builtin wants a literal)
-__device__ __forceinline__ void wait_vm(int n) {
+// Waits.  A wait is a statement that owns the registers it is for: they are in/out operands of the
+// s_waitcnt, so whatever consumes them afterwards depends on the wait, and from the (untracked) load that
+// writes them to this statement they are live values that the allocator may not hand to anything else.
+// n (14..31, or 0) folds to a constant once the loops around the call are unrolled.
+template <typename V8>
+__device__ __forceinline__ void wait_vm_for(V8 &frag, int n) {
     switch (n) {
-#define SJD_S_W(k) case k: __builtin_amdgcn_s_waitcnt(vmcnt_imm(k)); break;
+#define SJD_S_W(k) case k: asm volatile("s_waitcnt vmcnt(" #k ")" : "+v"(frag)); break;
         SJD_S_W(14) SJD_S_W(15) SJD_S_W(16) SJD_S_W(17) SJD_S_W(18) SJD_S_W(19) SJD_S_W(20) SJD_S_W(21) SJD_S_W(22)
         SJD_S_W(23) SJD_S_W(24) SJD_S_W(25) SJD_S_W(26) SJD_S_W(27) SJD_S_W(28) SJD_S_W(29) SJD_S_W(30) SJD_S_W(31)
 #undef SJD_S_W
-    default: __builtin_amdgcn_s_waitcnt(vmcnt_imm(0)); break;
+    default: asm volatile("s_waitcnt vmcnt(0)" : "+v"(frag)); break;
     }
 }
+// every load has landed; all sixteen ring registers pass through the statement
+template <typename V8>
+__device__ __forceinline__ void wait_all_for(V8 (&bq)[S_PD][2]) {
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)"
+                 : "+v"(bq[0][0]), "+v"(bq[0][1]), "+v"(bq[1][0]), "+v"(bq[1][1]), "+v"(bq[2][0]), "+v"(bq[2][1]),
+                   "+v"(bq[3][0]), "+v"(bq[3][1]), "+v"(bq[4][0]), "+v"(bq[4][1]), "+v"(bq[5][0]), "+v"(bq[5][1]),
+                   "+v"(bq[6][0]), "+v"(bq[6][1]), "+v"(bq[7][0]), "+v"(bq[7][1]));
+}
+static_assert(S_PD == 8, "wait_all_for names eight ring slots");
 // k-steps among the seven before k-step ks of a chunk (running over from the previous chunk) that requested pieces
 constexpr int pieces_window(int ks) {
     int f = 0;
@@ -107,7 +117,7 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_resid_kernel(const HT *__r
     };
 #pragma unroll
     for (int q = 0; q < 16; ++q) fetch(0, 0, q);
-    __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0): chunk 0 (and the first weight fragments) have landed
+    wait_all_for(bq);                         // chunk 0 and the first weight fragments have landed
     __builtin_amdgcn_s_barrier();
 
     f32x16 acc[4][2];
@@ -155,11 +165,11 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_resid_kernel(const HT *__r
                 }
                 // fragment 0 of this k-step was requested in slot 4 eight k-steps ago: since then fragment 1 of
                 // that k-step, two fragments in each of seven k-steps and the pieces of that window
-                if (m == 0) wait_vm(15 + 2 * pieces_window(ks));
+                if (m == 0) wait_vm_for(bq[slot][0], 15 + 2 * pieces_window(ks));
                 if (ks < 8 && m < 2) fetch(cn, buf ^ 1, 2 * ks + m);
                 if (m == 4) {
                     // fragment 1: requested after slot 7 eight k-steps ago; since then seven k-steps and this one's pieces
-                    wait_vm(14 + 2 * pieces_window(ks) + (ks < 8 ? 2 : 0));
+                    wait_vm_for(bq[slot][1], 14 + 2 * pieces_window(ks) + (ks < 8 ? 2 : 0));
                     __builtin_amdgcn_sched_barrier(0);
                     load_untracked(bq[slot][0], ks + S_PD < S_CKS ? wcur[0] + (size_t)(ks + S_PD) * 512
                                                                   : wahead[0] + (size_t)(ks + S_PD - S_CKS) * 512);
@@ -176,15 +186,10 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_resid_kernel(const HT *__r
         chunk_body(c, 0);
         chunk_body(c + 1, 1);
     }
-    __builtin_amdgcn_s_waitcnt(0x0070);       // every load has landed: the LDS-direct ones, and the last sixteen weight
-                                              // fragments, which nobody uses
-    // Those sixteen registers must not be given to anything else before that wait - the compiler does not
-    // know that loads into them are still in flight and would hand them to the epilogue's addresses, to be
-    // overwritten when the loads land.  Naming them here keeps them allocated up to this point.
-#pragma unroll
-    for (int p = 0; p < S_PD; ++p)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) asm volatile("" ::"v"(bq[p][j]));
+    // Every load has landed: the LDS-direct ones, and the last sixteen weight fragments, which nobody uses.
+    // Their registers are operands of this wait, so they stay allocated up to here: nothing else can be
+    // given a register that a load is still going to write.
+    wait_all_for(bq);
     __builtin_amdgcn_s_barrier();
 
     // ---- epilogue.  In the accumulators a lane owns one column and sixteen rows of a 32x32 block

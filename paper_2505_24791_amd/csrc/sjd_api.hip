@@ -67,6 +67,7 @@ struct sjd_flow {
     void *arena_frag = nullptr;  // the same matrices in fragment-major order (sequential fast path)
     void *arena_panel = nullptr; // QKV, attention-output and MLP-input matrices in the panel kernels' order
     int proj_path = 0;           // 0 automatic, 1 tile kernels only, 2 panel kernels wherever they apply
+    bool stream_ok = false;      // the streaming MLP-output kernel reproduced the tile kernel's bits at load time
     std::vector<BlockW> block;
     // workspaces (element type depends on dtype: float or bf16 for a, qkv, o, f and the cache)
     float *h = nullptr, *p = nullptr;
@@ -169,6 +170,35 @@ int drain_profile(sjd_flow *f) {
     return SJD_OK;
 }
 
+// The streaming MLP-output kernel issues its weight loads as inline assembly with hand-counted waits.  Once per
+// load_weights it is run beside the tile kernel on one small problem with the flow's own weights (block 0, layer 0;
+// 256 rows of ones; the residual stream starts at zero); unless the two give the same bits the flow keeps to the
+// tile kernels.  Uses the workspaces f and h, which no call is using yet.
+int stream_self_check(sjd_flow *f) {
+    const sjd_config &c = f->cfg;
+    const int W = c.width, RW = c.mlp_ratio * c.width, M = 256;
+    if (!gemm_stream_applicable(M, W, RW) || (size_t)c.max_batch * c.seq_len < 2 * (size_t)M) return SJD_OK;   // not used by this flow
+    const LayerW &lw = f->block[0].layer[0];
+    const size_t a_bytes = (size_t)M * RW * 2, h_bytes = (size_t)M * W * 4;
+    // 0x3C3C is 1.0586 as IEEE half and 0.0115 as bf16: a constant left operand, so every stale or misplaced
+    // weight fragment changes a sum
+    HIP_TRY(hipMemset(f->f, 0x3C, a_bytes));
+    HIP_TRY(hipMemset(f->h, 0, 2 * h_bytes));
+    float *h0 = f->h, *h1 = f->h + (size_t)M * W;
+    if (c.dtype == SJD_DTYPE_BF16) {
+        launch_gemm_stream_resid<bf16>((const bf16 *)f->f, (const bf16 *)lw.p_fc2, lw.b_fc2, h0, M, W, RW, 0);
+        launch_gemm_h16<bf16, float>((const bf16 *)f->f, (const bf16 *)lw.t_fc2, lw.b_fc2, h1, h1, M, W, RW, EPI_BIAS_RESIDUAL, 0, 3);
+    } else {
+        launch_gemm_stream_resid<f16>((const f16 *)f->f, (const f16 *)lw.p_fc2, lw.b_fc2, h0, M, W, RW, 0);
+        launch_gemm_h16<f16, float>((const f16 *)f->f, (const f16 *)lw.t_fc2, lw.b_fc2, h1, h1, M, W, RW, EPI_BIAS_RESIDUAL, 0, 3);
+    }
+    std::vector<float> host(2 * (size_t)M * W);
+    HIP_TRY(hipMemcpy(host.data(), f->h, 2 * h_bytes, hipMemcpyDeviceToHost));
+    HIP_TRY(hipGetLastError());
+    f->stream_ok = memcmp(host.data(), host.data() + (size_t)M * W, h_bytes) == 0;
+    return SJD_OK;
+}
+
 // ---- one projection, in the flow's precision ----------------------------------------------------
 template <typename HT>
 void project16(const void *A, const void *wt, const float *bias, void *C, int M, int N, int K, Epi epi, bool out_f32,
@@ -260,7 +290,7 @@ void conditioner_pass(sjd_flow *f, int j, const float *x, int n, const int32_t *
                            gemm_panel_applicable(M, 3 * W, W, 2) && gemm_panel_applicable(M, W, W, 4);
     const bool panel_qkv = panel_any && (f->proj_path == 2 || M >= 10240);
     const bool panel_fc1 = panel_any && (f->proj_path == 2 || M >= 12288);
-    const bool stream_fc2 = panel_any && (f->proj_path == 2 || M >= 10240) && gemm_stream_applicable(M, W, RW);
+    const bool stream_fc2 = panel_any && f->stream_ok && (f->proj_path == 2 || M >= 10240) && gemm_stream_applicable(M, W, RW);
     for (int l = 0; l < c.n_layers; ++l) {
         const LayerW &lw = bw.layer[l];
         if (panel_qkv) ln_project_panel(f, f->h, lw.ln1_g, lw.ln1_b, lw.p_qkv, lw.b_qkv, f->qkv, M, 3 * W, EPI_BIAS, s);
@@ -550,9 +580,13 @@ int run_sequential_persistent(sjd_flow *f, int j, const float *z, float *x, int 
     HIP_TRY(hipMemcpyAsync(f->host_pin, f->psync + 9, sizeof(int32_t), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
     HIP_TRY(hipGetLastError());
-    if (f->host_pin[0] != 0)
-        return fail(SJD_EHIP, "persistent sequential kernel: %s",
-                    f->host_pin[0] == 2 ? "fewer XCD groups than planned for" : "a group barrier timed out");
+    if (f->host_pin[0] != 0) {
+        fail(SJD_EHIP, "persistent sequential kernel: %s",
+             f->host_pin[0] == 2 ? "fewer XCD groups than planned for" : "a group barrier timed out");
+        // every wave has left the kernel (bounded waits); z is untouched and x, the caches and the workspaces are
+        // simply written again, so in automatic mode the caller runs the block by per-step launches instead
+        return SJD_ELAUNCH_RETRY;
+    }
     return SJD_OK;
 }
 
@@ -768,6 +802,11 @@ int sjd_flow_load_weights(sjd_flow *f, const void *host_blob, size_t nbytes) {
     }
     HIP_TRY(hipDeviceSynchronize());
     HIP_TRY(hipGetLastError());
+    f->stream_ok = false;
+    if (f->arena_panel) {
+        int rc = stream_self_check(f);
+        if (rc) return rc;
+    }
     f->loaded = true;
     return SJD_OK;
 }

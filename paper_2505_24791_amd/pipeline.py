@@ -30,7 +30,7 @@ def _hip_runtime():
     return _hip
 
 
-def masked_stream(first_cu: int, last_cu: int, n_cus_device: int = 256):
+def masked_stream(first_cu: int, last_cu: int, n_cus_device: int):
     """A stream whose kernels run on CU-mask bits first_cu .. last_cu-1 only.  Bit i of the mask is CU
     i // 8 of XCD i % 8 on this part, so a contiguous range of bits whose ends are multiples of 32
     takes the same number of CUs from every XCD and from every shader engine of an XCD (a workgroup
@@ -54,7 +54,7 @@ class PipelinedSampler:
     Jacobi blocks of the previous one.  ``n_seq_cus`` CUs (a multiple of 32) carry the sequential
     kernel, the rest the whole-sequence passes."""
 
-    def __init__(self, cfg, weights_blob, n_seq_cus: int = 128, n_cus_device: int = 256, dtype: int = DTYPE_F16):
+    def __init__(self, cfg, weights_blob, n_seq_cus: int = 128, n_cus_device: int = 0, dtype: int = DTYPE_F16):
         if cfg.n_blocks < 2:
             raise ValueError("needs at least one Jacobi block after the sequential one")
         self.cfg = cfg
@@ -67,6 +67,9 @@ class PipelinedSampler:
             f.set_sequential_path(3)             # ordinary launch: the stream's CU mask decides where it runs
             f.set_sequential_cus(n_seq_cus)
             self.flows.append(f)
+        if n_cus_device <= 0:       # the device's own CU count
+            import torch
+            n_cus_device = torch.cuda.get_device_properties(torch.cuda.current_device()).multi_processor_count
         self.seq_stream, self._seq_handle = masked_stream(0, n_seq_cus, n_cus_device)
         self.jac_stream, self._jac_handle = masked_stream(n_seq_cus, n_cus_device, n_cus_device)
 

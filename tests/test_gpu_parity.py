@@ -172,6 +172,9 @@ def test_bf16_conditioner_matches_oracle(torch_cuda, orc64, name, cfg, perturb, 
                 rmu, ral = rmu[::-1], ral[::-1]
             worst = max(worst, np.abs(mu[b] - rmu).max(), np.abs(al[b] - ral).max())
     print(f"{name} dtype {dtype}: worst conditioner error {worst:.3e}")
+    # One pass of the conditioner, not final samples: the bounds are this build's own, tighter than the 2e-2 that
+    # the task states for samples, and sit a factor of two above what these cases measure (IEEE half <= 3.0e-4,
+    # bf16 <= 2.3e-3: eight times coarser operands)
     assert worst <= (1e-3 if dtype == 2 else 5e-3)
     f.close()
 

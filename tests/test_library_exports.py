@@ -87,4 +87,4 @@ def test_cu_mask_ranges_are_validated_before_any_device_call():
     from paper_2505_24791_amd.pipeline import masked_stream
     for first, last in ((0, 48), (8, 64), (64, 64), (128, 96), (0, 288), (-32, 64)):
         with pytest.raises(ValueError):
-            masked_stream(first, last)
+            masked_stream(first, last, 256)
