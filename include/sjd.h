@@ -93,18 +93,23 @@ typedef struct {
 } sjd_stats;
 
 /* Timing of kernel families inside the library (for roofline reports).  Off by default. */
-#define SJD_PROF_GEMM 0        /* whole-sequence passes: the fused q/k/v projection */
+/* One family per kernel (template instantiation) that a profiler would list, so that a family's average launch
+ * time can be compared with a kernel trace directly. */
+#define SJD_PROF_GEMM 0        /* whole-sequence passes: the fused q/k/v projection (bias epilogue, 16-bit out) */
 #define SJD_PROF_ATTENTION 1   /* whole-sequence causal attention */
-#define SJD_PROF_EPILOGUE 2    /* fused affine update / difference reduction / convergence */
-#define SJD_PROF_DECODE_GEMM 3 /* projections of single-token steps */
+#define SJD_PROF_EPILOGUE 2    /* fused affine update / difference reduction / convergence; step advance of the sequential inverse */
+#define SJD_PROF_DECODE_GEMM 3 /* single-token steps: LayerNorm + q/k/v projection */
 #define SJD_PROF_DECODE_ATTN 4 /* KV-cached single-token attention */
 #define SJD_PROF_OTHER 5       /* embedding, LayerNorm, ... */
 #define SJD_PROF_DECODE_FUSED 6 /* the sequential inverse of a whole block as one persistent kernel */
-#define SJD_PROF_GEMM_O 7      /* whole-sequence passes: attention-output projection (residual epilogue) */
+#define SJD_PROF_GEMM_RESID 7  /* whole-sequence passes: attention-output and MLP-output projections (one kernel:
+                                  float32 residual epilogue; they differ in k) */
 #define SJD_PROF_GEMM_FC1 8    /* whole-sequence passes: MLP input projection (GELU epilogue) */
-#define SJD_PROF_GEMM_FC2 9    /* whole-sequence passes: MLP output projection (residual epilogue) */
+#define SJD_PROF_DECODE_RESID 9 /* single-token steps: attention-output and MLP-output projections */
 #define SJD_PROF_GEMM_HEAD 10  /* whole-sequence passes: the [mu | alpha] head */
-#define SJD_PROF_FAMILIES 11
+#define SJD_PROF_DECODE_FC1 11 /* single-token steps: LayerNorm + MLP input projection + GELU */
+#define SJD_PROF_DECODE_HEAD 12 /* single-token steps: final LayerNorm + head */
+#define SJD_PROF_FAMILIES 13
 typedef struct {
     double ms[SJD_PROF_FAMILIES];       /* summed device time per family since the last reset */
     int64_t launches[SJD_PROF_FAMILIES];

@@ -19,12 +19,13 @@ LIB_PATH = os.path.join(_HERE, "libsjd.so")
 SJD_OK, SJD_EINVAL, SJD_ENOMEM, SJD_EHIP, SJD_ENONFINITE, SJD_ESTATE = 0, -1, -2, -3, -4, -5
 SJD_MAX_BLOCKS = 32
 DTYPE_F32, DTYPE_BF16, DTYPE_F16 = 0, 1, 2
-(PROF_GEMM, PROF_ATTENTION, PROF_EPILOGUE, PROF_DECODE_GEMM, PROF_DECODE_ATTN, PROF_OTHER, PROF_DECODE_FUSED, PROF_GEMM_O,
- PROF_GEMM_FC1, PROF_GEMM_FC2, PROF_GEMM_HEAD) = range(11)
-PROF_FAMILIES = 11
-PROF_NAMES = ("gemm_qkv", "attention", "epilogue", "decode_gemm", "decode_attn", "other", "decode_fused", "gemm_o",
-              "gemm_fc1", "gemm_fc2", "gemm_head")
-PROF_GEMM_ALL = (PROF_GEMM, PROF_GEMM_O, PROF_GEMM_FC1, PROF_GEMM_FC2, PROF_GEMM_HEAD)   # every whole-sequence projection
+(PROF_GEMM, PROF_ATTENTION, PROF_EPILOGUE, PROF_DECODE_GEMM, PROF_DECODE_ATTN, PROF_OTHER, PROF_DECODE_FUSED,
+ PROF_GEMM_RESID, PROF_GEMM_FC1, PROF_DECODE_RESID, PROF_GEMM_HEAD, PROF_DECODE_FC1, PROF_DECODE_HEAD) = range(13)
+PROF_FAMILIES = 13
+PROF_NAMES = ("gemm_qkv", "attention", "epilogue", "decode_qkv", "decode_attn", "other", "decode_fused", "gemm_resid",
+              "gemm_fc1", "decode_resid", "gemm_head", "decode_fc1", "decode_head")
+PROF_GEMM_ALL = (PROF_GEMM, PROF_GEMM_RESID, PROF_GEMM_FC1, PROF_GEMM_HEAD)            # every whole-sequence projection
+PROF_DECODE_GEMM_ALL = (PROF_DECODE_GEMM, PROF_DECODE_RESID, PROF_DECODE_FC1, PROF_DECODE_HEAD)   # every single-token projection
 
 EXPORTS = ("sjd_flow_create", "sjd_flow_load_weights", "sjd_jacobi_inverse_block", "sjd_sequential_inverse_block",
            "sjd_sample", "sjd_conditioner", "sjd_op_linear_h16", "sjd_jacobi_trace_block", "sjd_forward_block",
@@ -330,12 +331,16 @@ class Flow:
         _check(self.lib.sjd_flow_set_sequential_cus(self._h, n_cus))
 
     def profile_enable(self, families) -> None:
-        """Family indices (PROF_*); PROF_GEMM stands for every whole-sequence projection family."""
+        """Family indices (PROF_*); PROF_GEMM / PROF_DECODE_GEMM stand for every whole-sequence / single-token
+        projection family."""
         mask = 0
         for f in families:
             mask |= 1 << f
             if f == PROF_GEMM:
                 for g in PROF_GEMM_ALL:
+                    mask |= 1 << g
+            if f == PROF_DECODE_GEMM:
+                for g in PROF_DECODE_GEMM_ALL:
                     mask |= 1 << g
         _check(self.lib.sjd_profile_enable(self._h, mask))
 
@@ -344,6 +349,8 @@ class Flow:
         _check(self.lib.sjd_profile_read(self._h, C.byref(p), 1 if reset else 0))
         out = {PROF_NAMES[i]: {"ms": p.ms[i], "launches": int(p.launches[i]), "flops": p.flops[i], "bytes": p.bytes[i]}
                for i in range(PROF_FAMILIES)}
-        # all whole-sequence projections together
+        # all whole-sequence projections together, all single-token projections together
         out["gemm"] = {k: sum(out[PROF_NAMES[g]][k] for g in PROF_GEMM_ALL) for k in ("ms", "launches", "flops", "bytes")}
+        out["decode_gemm"] = {k: sum(out[PROF_NAMES[g]][k] for g in PROF_DECODE_GEMM_ALL)
+                              for k in ("ms", "launches", "flops", "bytes")}
         return out

@@ -246,7 +246,7 @@ void ln_project_panel(sjd_flow *f, const float *H, const float *g, const float *
 void project_panel_resid(sjd_flow *f, const void *A, const void *wf, const float *bias, float *H, int M, int N,
                          hipStream_t s) {
     const int W = f->cfg.width;
-    ProfScope ps(f, SJD_PROF_GEMM_O, 2.0 * M * (double)N * W, (double)M * W * 2.0 + (double)W * N * 2.0 + (double)M * N * 8.0 + N * 4.0, s);
+    ProfScope ps(f, SJD_PROF_GEMM_RESID, 2.0 * M * (double)N * W, (double)M * W * 2.0 + (double)W * N * 2.0 + (double)M * N * 8.0 + N * 4.0, s);
     if (f->cfg.dtype == SJD_DTYPE_BF16) launch_gemm_panel_resid<bf16>((const bf16 *)A, (const bf16 *)wf, bias, H, M, N, s);
     else launch_gemm_panel_resid<f16>((const f16 *)A, (const f16 *)wf, bias, H, M, N, s);
 }
@@ -306,17 +306,17 @@ void conditioner_pass(sjd_flow *f, int j, const float *x, int n, const int32_t *
             else attention_full<float>(f->qkv, f->o, n, T, W, H, f->mask_nearest, s);
         }
         if (panel_qkv) project_panel_resid(f, f->o, lw.p_o, lw.b_o, f->h, M, W, s);
-        else project(f, SJD_PROF_GEMM_O, f->o, lw.w_o, lw.t_o, lw.b_o, f->h, M, W, W, EPI_BIAS_RESIDUAL, true, s);
+        else project(f, SJD_PROF_GEMM_RESID, f->o, lw.w_o, lw.t_o, lw.b_o, f->h, M, W, W, EPI_BIAS_RESIDUAL, true, s);
         if (panel_fc1) ln_project_panel(f, f->h, lw.ln2_g, lw.ln2_b, lw.p_fc1, lw.b_fc1, f->f, M, RW, EPI_BIAS_GELU, s);
         else {
             layernorm(f, f->h, lw.ln2_g, lw.ln2_b, f->a, M, s);
             project(f, SJD_PROF_GEMM_FC1, f->a, lw.w_fc1, lw.t_fc1, lw.b_fc1, f->f, M, RW, W, EPI_BIAS_GELU, false, s);
         }
         if (stream_fc2) {
-            ProfScope ps(f, SJD_PROF_GEMM_FC2, 2.0 * M * (double)W * RW, (double)M * RW * 2.0 + (double)RW * W * 2.0 + (double)M * W * 8.0 + W * 4.0, s);
+            ProfScope ps(f, SJD_PROF_GEMM_RESID, 2.0 * M * (double)W * RW, (double)M * RW * 2.0 + (double)RW * W * 2.0 + (double)M * W * 8.0 + W * 4.0, s);
             if (c.dtype == SJD_DTYPE_BF16) launch_gemm_stream_resid<bf16>((const bf16 *)f->f, (const bf16 *)lw.p_fc2, lw.b_fc2, f->h, M, W, RW, s);
             else launch_gemm_stream_resid<f16>((const f16 *)f->f, (const f16 *)lw.p_fc2, lw.b_fc2, f->h, M, W, RW, s);
-        } else project(f, SJD_PROF_GEMM_FC2, f->f, lw.w_fc2, lw.t_fc2, lw.b_fc2, f->h, M, W, RW, EPI_BIAS_RESIDUAL, true, s);
+        } else project(f, SJD_PROF_GEMM_RESID, f->f, lw.w_fc2, lw.t_fc2, lw.b_fc2, f->h, M, W, RW, EPI_BIAS_RESIDUAL, true, s);
     }
     layernorm(f, f->h, bw.lnf_g, bw.lnf_b, f->a, M, s);
     project(f, SJD_PROF_GEMM_HEAD, f->a, bw.w_head, bw.t_head, bw.b_head, f->p, M, 2 * D, W, EPI_BIAS, true, s);
@@ -448,7 +448,8 @@ void fast_step(sjd_flow *f, int j, const float *z, float *x, int B, bool frag, h
     // LayerNorm + projection: fused when the operands are fragment-major, else two launches
     auto ln_project = [&](const float *g, const float *be, const void *wt, const void *wf, const float *bias, void *out,
                           int N, Epi epi, bool out_f32) {
-        ProfScope ps(f, SJD_PROF_DECODE_GEMM, 2.0 * B * (double)N * W, gemm_bytes(N, W, out_f32 ? 4 : 2), s);
+        ProfScope ps(f, out_f32 ? SJD_PROF_DECODE_HEAD : (epi == EPI_BIAS_GELU ? SJD_PROF_DECODE_FC1 : SJD_PROF_DECODE_GEMM),
+                     2.0 * B * (double)N * W, gemm_bytes(N, W, out_f32 ? 4 : 2), s);
         if (frag) {
             bool ok = out_f32 ? launch_skinny_ln_gemm<HT, float>(f->h, g, be, (const HT *)wf, bias, (float *)out, B, N, W, epi, s)
                               : launch_skinny_ln_gemm<HT, HT>(f->h, g, be, (const HT *)wf, bias, (HT *)out, B, N, W, epi, s);
@@ -470,13 +471,13 @@ void fast_step(sjd_flow *f, int j, const float *z, float *x, int B, bool frag, h
                                             T, H, frag, s);
         }
         {
-            ProfScope ps(f, SJD_PROF_DECODE_GEMM, 2.0 * B * (double)W * W, gemm_bytes(W, W, 8), s);
+            ProfScope ps(f, SJD_PROF_DECODE_RESID, 2.0 * B * (double)W * W, gemm_bytes(W, W, 8), s);
             launch_skinny_gemm<HT, float>(o, (const HT *)(frag ? lw.f_o : lw.t_o), lw.b_o, f->h, f->h, B, W, W,
                                           EPI_BIAS_RESIDUAL, frag, s);
         }
         ln_project(lw.ln2_g, lw.ln2_b, lw.t_fc1, lw.f_fc1, lw.b_fc1, ff, RW, EPI_BIAS_GELU, false);
         {
-            ProfScope ps(f, SJD_PROF_DECODE_GEMM, 2.0 * B * (double)RW * W, gemm_bytes(W, RW, 8), s);
+            ProfScope ps(f, SJD_PROF_DECODE_RESID, 2.0 * B * (double)RW * W, gemm_bytes(W, RW, 8), s);
             launch_skinny_gemm<HT, float>(ff, (const HT *)(frag ? lw.f_fc2 : lw.t_fc2), lw.b_fc2, f->h, f->h, B, W, RW,
                                           EPI_BIAS_RESIDUAL, frag, s);
         }
