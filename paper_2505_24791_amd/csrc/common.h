@@ -222,7 +222,8 @@ void launch_decode_advance(const float *p, const float *z, float *x, const float
 
 // Jacobi epilogue.  p [n_rows, 2D] head output (row r of a sample parameterises position r+1).
 // For every listed sample that is still active: x <- z*exp(alpha)+mu in place, delta, pass count,
-// convergence flag.  Then the last workgroup rebuilds the active list.
+// convergence flag.  Then the last workgroup rebuilds the active list.  shared_params != 0: p holds the head output
+// of ONE sample, [T, 2D], which parameterises every listed sample (see run_jacobi: the pass from x^0 = 0).
 struct JacobiState {
     float *delta;          // [B] last delta of each sample
     int32_t *iters;        // [B] passes taken
@@ -234,7 +235,8 @@ struct JacobiState {
     uint32_t *ticket;      // [1] workgroup counter, zero before the launch, zero again after
 };
 void launch_jacobi_epilogue(const float *p, const float *z, float *x, JacobiState st, int n_listed, int T, int D,
-                            int reversed, float tau, int criterion, int cap, int drop_converged, hipStream_t s);
+                            int reversed, float tau, int criterion, int cap, int drop_converged, int shared_params,
+                            hipStream_t s);
 
 // x^0 and state initialisation for a Jacobi block: x = 0 or z; iters = 0; done = 0; active = 0..B-1
 void launch_jacobi_init(const float *z, float *x, JacobiState st, int B, int T, int D, int init, hipStream_t s);

@@ -518,19 +518,20 @@ template void launch_decode_attention_h16<f16>(const f16 *, f16 *, f16 *, f16 *,
 // position l = t+1 of every sample, x_l = z_l * exp(alpha) + mu (eq. 5), then embed it,
 // h[b, :] = x_l * w_in + b_in + pos[l, :].  With first != 0: l = 0, x_0 = z_0 and t is set to 0.
 // The workgroup that finishes last advances the step counter.
-__global__ __launch_bounds__(256) void decode_advance_kernel(const float *__restrict__ p, const float *__restrict__ z,
-                                                             float *__restrict__ x, const float *__restrict__ w_in,
-                                                             const float *__restrict__ b_in,
-                                                             const float *__restrict__ pos, float *__restrict__ h,
-                                                             int32_t *t_dev, uint32_t *ticket, int T, int D, int W,
-                                                             int reversed, int first, int frag) {
+__global__ __launch_bounds__(1024) void decode_advance_kernel(const float *__restrict__ p, const float *__restrict__ z,
+                                                              float *__restrict__ x, const float *__restrict__ w_in,
+                                                              const float *__restrict__ b_in,
+                                                              const float *__restrict__ pos, float *__restrict__ h,
+                                                              int32_t *t_dev, uint32_t *ticket, int T, int D, int W,
+                                                              int reversed, int first, int frag) {
     extern __shared__ float xs[];
     const int b = blockIdx.x;
+    const int nt = blockDim.x;
     const int t = first ? -1 : *t_dev;
     const int l = t + 1;
     if (l < T) {
         const int tok = reversed ? T - 1 - l : l;
-        for (int d = threadIdx.x; d < D; d += 256) {
+        for (int d = threadIdx.x; d < D; d += nt) {
             const size_t idx = ((size_t)b * T + tok) * D + d;
             float xn = z[idx];
             if (l > 0) xn = fmaf(xn, expf(p[(size_t)b * 2 * D + D + d]), p[(size_t)b * 2 * D + d]);
@@ -538,21 +539,22 @@ __global__ __launch_bounds__(256) void decode_advance_kernel(const float *__rest
             xs[d] = xn;
         }
         __syncthreads();
-        for (int w = threadIdx.x; w < W; w += 256) {
+        for (int w = threadIdx.x; w < W; w += nt) {
             float acc = b_in[w];
-            // eight rows of the embedding matrix are requested before the first is used (one dependent round
+            const float pw = pos[(size_t)l * W + w];
+            // sixteen rows of the embedding matrix are requested before the first is used (one dependent round
             // trip per row otherwise); the sum still runs over d in index order
             int d = 0;
-            for (; d + 8 <= D; d += 8) {
-                float wv[8];
+            for (; d + 16 <= D; d += 16) {
+                float wv[16];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) wv[u] = w_in[(size_t)(d + u) * W + w];
+                for (int u = 0; u < 16; ++u) wv[u] = w_in[(size_t)(d + u) * W + w];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) acc = fmaf(xs[d + u], wv[u], acc);
+                for (int u = 0; u < 16; ++u) acc = fmaf(xs[d + u], wv[u], acc);
             }
             for (; d < D; ++d) acc = fmaf(xs[d], w_in[(size_t)d * W + w], acc);
             const size_t ho = frag ? frag_off(b, w, W / 32) : (size_t)b * W + w;
-            h[ho] = acc + pos[(size_t)l * W + w];
+            h[ho] = acc + pw;
         }
     }
     __syncthreads();
@@ -570,8 +572,11 @@ void launch_decode_advance(const float *p, const float *z, float *x, const float
                            const float *pos, float *h, int32_t *t_dev, uint32_t *ticket, int B, int T, int D, int W,
                            int reversed, int first, bool frag, hipStream_t s) {
     if (B <= 0) return;
-    hipLaunchKernelGGL(decode_advance_kernel, dim3(B), dim3(256), D * sizeof(float), s, p, z, x, w_in, b_in, pos, h, t_dev,
-                       ticket, T, D, W, reversed, first, frag ? 1 : 0);
+    // one thread per column of the embedding where the width allows: a thread's columns are walked one after
+    // the other, each costing its own round trips to L2
+    const int threads = W >= 1024 ? 1024 : (W >= 512 ? 512 : 256);
+    hipLaunchKernelGGL(decode_advance_kernel, dim3(B), dim3(threads), D * sizeof(float), s, p, z, x, w_in, b_in, pos, h,
+                       t_dev, ticket, T, D, W, reversed, first, frag ? 1 : 0);
 }
 
 }  // namespace sjd

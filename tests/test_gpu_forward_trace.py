@@ -164,3 +164,31 @@ def test_convergence_record_matches_oracle(torch_cuda, orc32, cfg, tol):
         _, _, passes, delta, err = f.jacobi_trace_block(0, zd, sjd.JacobiOpts(tau=0.0), x_ref=xref)
         assert passes == cfg.seq_len and err[-1].max() <= 1e-4
     f.close()
+
+
+@pytest.mark.parametrize("case", ["f32", "half_ragged", "half_c2_shape"])
+def test_first_pass_shared_over_the_batch_gives_the_same_bits(case):
+    """Alg. 1 starts every sample from x^0 = 0, so the first pass's parameters are the same for all samples and
+    the library computes them on one sample's rows.  A caller-supplied all-zero first iterate takes the ordinary
+    path (every sample through the conditioner): iterates and pass counts must agree bit for bit, in float32, on
+    a ragged 16-bit shape, and at configuration 2's shape (where the full pass and the one-sample pass take
+    different projection kernels)."""
+    import torch
+    import paper_2505_24791_amd as sjd
+    if case == "f32":
+        cfg = wl.CONFIGS["C1"]
+    elif case == "half_ragged":
+        cfg = wl.FlowConfig("r", n_blocks=2, n_layers=2, width=128, n_heads=2, seq_len=70, token_dim=6, batch=9, bf16=True)
+    else:
+        cfg = wl.CONFIGS["C2"].with_(n_blocks=2, batch=48)
+    blob = wl.make_weights(cfg, perturb_affine=(case != "half_c2_shape"))
+    z = torch.from_numpy(wl.make_latent(cfg)).cuda()
+    f = sjd.Flow(cfg)
+    f.load_weights(blob)
+    for j in range(cfg.n_blocks):
+        for cap in (1, 0):
+            xa, ia, pa, _ = f.jacobi_inverse_block(j, z, sjd.JacobiOpts(tau=cfg.tau, init=0, max_iters=cap))
+            xb, ib, pb, _ = f.jacobi_inverse_block(j, z, sjd.JacobiOpts(tau=cfg.tau, init=2, max_iters=cap), x0=torch.zeros_like(z))
+            assert torch.equal(xa, xb), (case, j, cap)
+            assert np.array_equal(ia, ib) and pa == pb
+    f.close()
