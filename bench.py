@@ -37,10 +37,10 @@ def measured_traffic(workload: str, family: str):
             text = open(path).read()
         except OSError:
             continue
-        for m in re.finditer(r"^TRAFFIC\s+(\S+)\s+(\S+)\s+([0-9.eE+]+)\s*$", text, re.M):
+        for m in re.finditer(r"^TRAFFIC\s+(\S+)\s+(\S+)\s+([0-9.eE+]+)(?:\s+([0-9.eE+]+))?\s*$", text, re.M):
             if m.group(1) == workload and m.group(2) == family:
-                return float(m.group(3))
-    return None
+                return float(m.group(3)), (float(m.group(4)) if m.group(4) else None), os.path.relpath(path, ROOT)
+    return None, None, None
 
 
 def parse():
@@ -87,8 +87,9 @@ def parse():
                          "cascade for C1/C2, block 0 plus two Jacobi passes of block 1 for the larger workloads)")
     ap.add_argument("--counters", action="store_true",
                     help="for runs under rocprofv3 --pmc: a plain 256 MiB device copy five times (the known-size "
-                         "kernel that hardware traffic counters are scaled by), then block 0 sequentially and ONE "
-                         "whole-sequence Jacobi pass of block 1, progress on stderr, no timing")
+                         "kernel that hardware traffic counters are scaled by), then block 0 sequentially (only where it "
+                         "is one persistent kernel) and ONE whole-sequence Jacobi pass of block 1 at the full batch, "
+                         "progress on stderr, no timing")
     return ap.parse_args()
 
 
@@ -157,8 +158,9 @@ def main() -> int:
             # per-step launches are tens of thousands of dispatches (the profiler's counter mode does not survive
             # them): the whole-sequence pass below gets the latent itself as its input, which moves the same bytes
             say("block 0 skipped (per-step launches)")
-        # one whole-sequence pass at the full batch is enough for the per-launch traffic of its kernels
-        one = sjd.JacobiOpts(tau=tau, max_iters=1)
+        # one whole-sequence pass at the full batch is enough for the per-launch traffic of its kernels (first
+        # iterate = the block's input: from the all-zero iterate the library would run the pass on one sample only)
+        one = sjd.JacobiOpts(tau=tau, max_iters=1, init=1)
         flow.jacobi_inverse_block(1 if K > 1 else 0, cur, one)
         say("one Jacobi pass of the next block done")
         flow.close()
@@ -212,7 +214,11 @@ def main() -> int:
         roof = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": achieved / PEAK_HBM_GBS, "traffic": None}
     if not (args.batch or args.seq_len):
-        roof["traffic"] = measured_traffic(cfg.name, dominant)
+        # counters are collected on full-batch launches; `achieved` averages over every launch of a step (late passes
+        # run on fewer samples), so the algorithmic bytes of the measured launches are given beside the traffic
+        roof["traffic"], alg, src = measured_traffic(cfg.name, dominant)
+        if src:
+            roof["traffic_of"] = {"launch": "full batch (every sample active)", "algorithmic_bytes": alg, "summary": src}
     roof.update({"kernel_family": dominant, "algorithmic_bytes_per_launch": d["bytes"] / launches,
                  "algorithmic_flops_per_launch": d["flops"] / launches, "launches_per_step": launches / args.steps,
                  "avg_launch_us": avg_s * 1e6, "family_ms_per_step": fam_ms})

@@ -144,15 +144,21 @@ constexpr int FA_VS = FA_BK;       // V^T tile row stride (elements)
 
 template <typename HT>
 __global__ __launch_bounds__(256, 2) void flash_attention_h16_kernel(const HT *__restrict__ qkv, HT *__restrict__ o,
-                                                                  int T, int H, float scale_log2) {
+                                                                  int T, int H, int n_pairs, float scale_log2) {
     typedef typename Half16<HT>::v8 v8;
     typedef typename Half16<HT>::v4 v4;
     __shared__ __attribute__((aligned(16))) HT Ks[FA_BK * FA_KS];
     __shared__ __attribute__((aligned(16))) HT Vt[FA_DH * FA_VS];
     const int W = H * FA_DH;
     const int n_qt = (T + FA_BQ - 1) / FA_BQ;
-    const int qt = n_qt - 1 - (int)blockIdx.x;  // heavy tiles first
-    const int h = blockIdx.y, i = blockIdx.z;
+    // Workgroups go to the eight XCDs round robin by their linear index, and each XCD has an L2 of its own:
+    // the query tiles of one (sample, head) take consecutive slots of ONE XCD, so its keys and values come
+    // from memory once and the other tiles find them in that L2.
+    const int slot = (int)blockIdx.x >> 3;
+    const int pair = (slot / n_qt) * 8 + ((int)blockIdx.x & 7);
+    if (pair >= n_pairs) return;                // the grid is padded to a multiple of eight pairs
+    const int qt = n_qt - 1 - slot % n_qt;      // heavy tiles first
+    const int h = pair % H, i = pair / H;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, g = lane >> 5;
     const HT *base = qkv + (size_t)i * T * 3 * W;
@@ -306,7 +312,9 @@ void launch_flash_attention_h16(const HT *qkv, HT *o, int n_samples, int T, int 
     if (n_samples <= 0) return;
     const int n_qt = (T + FA_BQ - 1) / FA_BQ;
     const float scale_log2 = 1.4426950408889634f / sqrtf((float)FA_DH);
-    hipLaunchKernelGGL(flash_attention_h16_kernel<HT>, dim3(n_qt, H, n_samples), dim3(256), 0, s, qkv, o, T, H, scale_log2);
+    const int n_pairs = n_samples * H;
+    const unsigned grid = (unsigned)((n_pairs + 7) / 8) * 8u * (unsigned)n_qt;
+    hipLaunchKernelGGL(flash_attention_h16_kernel<HT>, dim3(grid), dim3(256), 0, s, qkv, o, T, H, n_pairs, scale_log2);
 }
 template void launch_flash_attention_h16<bf16>(const bf16 *, bf16 *, int, int, int, hipStream_t);
 template void launch_flash_attention_h16<f16>(const f16 *, f16 *, int, int, int, hipStream_t);
