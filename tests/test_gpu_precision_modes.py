@@ -1,7 +1,7 @@
 """What the three arithmetic modes deliver at workload scale: configuration 2 at its real shape on the
 first samples of the batch, against the float32 CPU oracle.  Needs an MI355X.
 
-The record these tests pin (measured on the MI355X; the figures are repeated in the design doc):
+The record these tests pin (measured on the MI355X):
 
   mode            all-sequential sample   selective, tau = 1e-3          selective, tau = 1e-4
   float32         err 1e-5                err 1e-5, oracle's counts      err 1e-5, oracle's counts
@@ -75,7 +75,7 @@ def test_half_mode_is_exact_in_the_counts_at_tau_1e_3_and_floor_limited_at_1e_4(
     # under the noise floor of the mode: never earlier than the oracle, far later, and the samples stay accurate
     assert err_sel <= 2e-2
     assert (iters[1:] >= riters[1:]).all()
-    assert iters[1:].min() >= 3 * riters[1:].max(), "the floor moved: revisit the record in this file and in DESIGN.md"
+    assert iters[1:].min() >= 3 * riters[1:].max(), "the floor moved: revisit the record at the top of this file"
     assert iters[1:].max() < c2[0].seq_len, "every sample still stops by its own test, none runs to the cap"
 
 
