@@ -84,6 +84,13 @@ typedef struct {
     int32_t max_iters;      /* 0 or >= T: the cap is T (Prop. 3.2: the T-th iterate is exact); else a lower cap */
     int32_t drop_converged; /* 1: converged samples leave the batch the conditioner runs on;  0: they stay
                                (and are ignored).  Results and counts are the same either way. */
+    float refine_below;     /* 16-bit flows only; 0: off.  A sample whose delta has fallen below this level runs its
+                               remaining passes of the block in float32 arithmetic (float32 weights and activations).
+                               The rounding of 16-bit operands keeps delta from falling much below 1e-4 (IEEE half) or
+                               1e-3 (bf16): with tau under that floor, set this a few times above it (1e-3 for half)
+                               and the pass counts follow exact arithmetic again.  Per sample, so a sample's result
+                               still does not depend on the batch.  The first use allocates float32 workspaces for
+                               about 8192 rows in the handle. */
 } sjd_jacobi_opts;
 
 typedef struct {

@@ -41,7 +41,7 @@ class SjdConfig(C.Structure):
 
 class SjdJacobiOpts(C.Structure):
     _fields_ = [("tau", C.c_float), ("criterion", C.c_int32), ("init", C.c_int32), ("max_iters", C.c_int32),
-                ("drop_converged", C.c_int32)]
+                ("drop_converged", C.c_int32), ("refine_below", C.c_float)]
 
 
 class SjdStats(C.Structure):
@@ -116,9 +116,11 @@ class JacobiOpts:
     init: int = 0
     max_iters: int = 0
     drop_converged: int = 1
+    refine_below: float = 0.0
 
     def c(self) -> SjdJacobiOpts:
-        return SjdJacobiOpts(self.tau, self.criterion, self.init, self.max_iters, self.drop_converged)
+        return SjdJacobiOpts(self.tau, self.criterion, self.init, self.max_iters, self.drop_converged,
+                             self.refine_below)
 
 
 def _stream_ptr() -> Optional[int]:

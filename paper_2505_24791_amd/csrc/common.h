@@ -231,12 +231,18 @@ struct JacobiState {
     int32_t *nonfinite;    // [1] set when a sample finishes with a non-finite delta
     int32_t *active_in;    // [B] samples this pass ran on (n_listed entries)
     int32_t *active_out;   // [B] compacted list of samples still running
-    int32_t *n_active_out; // [1]
+    int32_t *n_active_out; // [2] samples still running; how many of them are marked fine (they end the list)
     uint32_t *ticket;      // [1] workgroup counter, zero before the launch, zero again after
+    int32_t *fine;         // [B] 1 once a sample's delta has fallen below the refinement level (it stays 1)
 };
-void launch_jacobi_epilogue(const float *p, const float *z, float *x, JacobiState st, int n_listed, int T, int D,
-                            int reversed, float tau, int criterion, int cap, int drop_converged, int shared_params,
-                            hipStream_t s);
+// The update of Alg. 1 for the n samples listed in st.active_in (head output p: row block i belongs to entry i;
+// with shared_params one sample's parameters serve all): x <- z * exp(alpha) + mu, delta, pass count, done flag;
+// a sample whose delta falls below refine_below is marked fine.
+void launch_jacobi_update(const float *p, const float *z, float *x, JacobiState st, int n, int T, int D, int reversed,
+                          float tau, int criterion, int cap, int shared_params, float refine_below, hipStream_t s);
+// Rebuilds the list of samples that still iterate: first those not marked fine, then the fine ones, each part in
+// increasing order; st.n_active_out receives both counts.  keep_all: finished samples stay listed (first part).
+void launch_jacobi_compact(JacobiState st, int n_listed, int keep_all, hipStream_t s);
 
 // x^0 and state initialisation for a Jacobi block: x = 0 or z; iters = 0; done = 0; active = 0..B-1
 void launch_jacobi_init(const float *z, float *x, JacobiState st, int B, int T, int D, int init, hipStream_t s);

@@ -158,7 +158,7 @@ __device__ __forceinline__ float nan_max(float a, float d) { return (d > a || d 
 __global__ __launch_bounds__(256) void jacobi_epilogue_kernel(const float *__restrict__ p, const float *__restrict__ z,
                                                               float *__restrict__ x, JacobiState st, int T, int D,
                                                               int reversed, float tau, int criterion, int cap,
-                                                              int shared_params) {
+                                                              int shared_params, float refine_below) {
     __shared__ float part[4];
     const int i = blockIdx.x;
     const int b = st.active_in[i];
@@ -219,46 +219,61 @@ __global__ __launch_bounds__(256) void jacobi_epilogue_kernel(const float *__res
             st.done[b] = 1;
             if (!(fabsf(delta) <= 3.0e38f)) *st.nonfinite = 1;
         }
+        if (delta < refine_below) st.fine[b] = 1;
     }
 }
 
-// Rebuilds the list of samples that still iterate (in increasing order) and counts them.
-// With keep_all the list is left complete and only the count of unfinished samples is produced.
+// Rebuilds the list of samples that still iterate and counts them: first the samples that are not marked
+// fine, then the fine ones (their passes run in float32), each part in increasing order of the sample index.
+// With keep_all the list is left complete (finished samples go with the first part) and only the counts of
+// unfinished samples are produced.
 __global__ __launch_bounds__(256) void compact_active_kernel(JacobiState st, int n_listed, int keep_all) {
     __shared__ int wave_keep[4], wave_live[4];
-    __shared__ int base_keep, base_live;
+    __shared__ int base_keep, base_live, base_fine;
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    if (threadIdx.x == 0) { base_keep = 0; base_live = 0; }
+    if (threadIdx.x == 0) { base_keep = 0; base_live = 0; base_fine = 0; }
     __syncthreads();
-    for (int start = 0; start < n_listed; start += 256) {
-        const int i = start + threadIdx.x;
-        int b = -1, live = 0;
-        if (i < n_listed) { b = st.active_in[i]; live = st.done[b] ? 0 : 1; }
-        const int keep = (i < n_listed) && (keep_all || live);
-        const unsigned long long mk = __ballot(keep), ml = __ballot(live);
-        const int before = __popcll(mk & ((1ull << lane) - 1ull));
-        if (lane == 0) { wave_keep[wv] = __popcll(mk); wave_live[wv] = __popcll(ml); }
-        __syncthreads();
-        int off = base_keep;
-        for (int w = 0; w < wv; ++w) off += wave_keep[w];
-        if (keep) st.active_out[off + before] = b;
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            base_keep += wave_keep[0] + wave_keep[1] + wave_keep[2] + wave_keep[3];
-            base_live += wave_live[0] + wave_live[1] + wave_live[2] + wave_live[3];
+    for (int part = 0; part < 2; ++part) {
+        for (int start = 0; start < n_listed; start += 256) {
+            const int i = start + threadIdx.x;
+            int b = -1, live = 0;
+            if (i < n_listed) {
+                b = st.active_in[i];
+                const int alive = st.done[b] ? 0 : 1;
+                const int fine = alive && st.fine[b];
+                live = alive && fine == part;
+            }
+            const int keep = live || (part == 0 && keep_all && i < n_listed && st.done[b]);
+            const unsigned long long mk = __ballot(keep), ml = __ballot(live);
+            const int before = __popcll(mk & ((1ull << lane) - 1ull));
+            if (lane == 0) { wave_keep[wv] = __popcll(mk); wave_live[wv] = __popcll(ml); }
+            __syncthreads();
+            int off = base_keep;
+            for (int w = 0; w < wv; ++w) off += wave_keep[w];
+            if (keep) st.active_out[off + before] = b;
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                const int lv = wave_live[0] + wave_live[1] + wave_live[2] + wave_live[3];
+                base_keep += wave_keep[0] + wave_keep[1] + wave_keep[2] + wave_keep[3];
+                base_live += lv;
+                if (part == 1) base_fine += lv;
+            }
+            __syncthreads();
         }
-        __syncthreads();
     }
-    if (threadIdx.x == 0) *st.n_active_out = base_live;
+    if (threadIdx.x == 0) { st.n_active_out[0] = base_live; st.n_active_out[1] = base_fine; }
 }
 
-void launch_jacobi_epilogue(const float *p, const float *z, float *x, JacobiState st, int n_listed, int T, int D,
-                            int reversed, float tau, int criterion, int cap, int drop_converged, int shared_params,
-                            hipStream_t s) {
+void launch_jacobi_update(const float *p, const float *z, float *x, JacobiState st, int n, int T, int D, int reversed,
+                          float tau, int criterion, int cap, int shared_params, float refine_below, hipStream_t s) {
+    if (n <= 0) return;
+    hipLaunchKernelGGL(jacobi_epilogue_kernel, dim3(n), dim3(256), 0, s, p, z, x, st, T, D, reversed, tau, criterion,
+                       cap, shared_params, refine_below);
+}
+
+void launch_jacobi_compact(JacobiState st, int n_listed, int keep_all, hipStream_t s) {
     if (n_listed <= 0) return;
-    hipLaunchKernelGGL(jacobi_epilogue_kernel, dim3(n_listed), dim3(256), 0, s, p, z, x, st, T, D, reversed, tau,
-                       criterion, cap, shared_params);
-    hipLaunchKernelGGL(compact_active_kernel, dim3(1), dim3(256), 0, s, st, n_listed, drop_converged ? 0 : 1);
+    hipLaunchKernelGGL(compact_active_kernel, dim3(1), dim3(256), 0, s, st, n_listed, keep_all);
 }
 
 __global__ __launch_bounds__(256) void jacobi_init_kernel(const float *__restrict__ z, float *__restrict__ x,
@@ -268,9 +283,9 @@ __global__ __launch_bounds__(256) void jacobi_init_kernel(const float *__restric
         if (init != 2) x[e] = init == 1 ? z[e] : 0.f;   // init 2: the caller's x^0 is already in x
     if (blockIdx.x == 0) {
         for (int b = threadIdx.x; b < B; b += 256) {
-            st.iters[b] = 0; st.done[b] = 0; st.delta[b] = 0.f; st.active_in[b] = b; st.active_out[b] = b;
+            st.iters[b] = 0; st.done[b] = 0; st.fine[b] = 0; st.delta[b] = 0.f; st.active_in[b] = b; st.active_out[b] = b;
         }
-        if (threadIdx.x == 0) { *st.n_active_out = B; *st.nonfinite = 0; }
+        if (threadIdx.x == 0) { st.n_active_out[0] = B; st.n_active_out[1] = 0; *st.nonfinite = 0; }
     }
 }
 

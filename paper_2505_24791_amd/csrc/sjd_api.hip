@@ -77,7 +77,11 @@ struct sjd_flow {
     JacobiState st{};
     int32_t *active[2] = {nullptr, nullptr};
     float *trace = nullptr;                     // per-pass record: delta [T][B], then l2 error [T][B]
-    int32_t *host_pin = nullptr;                // pinned: [0] n_active, [1] nonfinite, [2..] iters[B]
+    // float32 activation workspaces of a 16-bit flow for refined passes (sjd_jacobi_opts.refine_below), allocated
+    // on first use for r32_samples samples at a time
+    void *r32_a = nullptr, *r32_qkv = nullptr, *r32_o = nullptr, *r32_f = nullptr;
+    int r32_samples = 0;
+    int32_t *host_pin = nullptr;                // pinned: [0] n_active, [1] n_fine, [2] nonfinite, [3..] iters[B]
     // sequential fast path: device step counter, ticket, capture stream, one graph per (block, batch)
     int32_t *t_dev = nullptr;
     uint32_t *ticket = nullptr;
@@ -404,12 +408,40 @@ int check_opts(const sjd_jacobi_opts *o) {
     if (o->criterion != 0 && o->criterion != 1) return fail(SJD_EINVAL, "criterion must be 0 or 1");
     if (o->init < 0 || o->init > 2) return fail(SJD_EINVAL, "init must be 0 (zeros), 1 (block input) or 2 (x_dev as passed)");
     if (o->max_iters < 0) return fail(SJD_EINVAL, "max_iters is negative");
+    if (!(o->refine_below >= 0.f)) return fail(SJD_EINVAL, "refine_below is negative or NaN");
     return SJD_OK;
 }
 
 // Alg. 1 for one block.  iters_pin (pinned host, [batch]) receives per-sample pass counts.
 // With `trace` every pass also records each sample's delta and (x_ref given) the l2 distance of its
 // newest iterate to x_ref into f->trace.
+// Float32 workspaces for refined passes of a 16-bit flow: about 8192 rows at a time.
+int ensure_refine_workspace(sjd_flow *f) {
+    if (f->r32_samples) return SJD_OK;
+    const sjd_config &c = f->cfg;
+    int n = 8192 / c.seq_len;
+    n = n < 1 ? 1 : (n > c.max_batch ? c.max_batch : n);
+    const size_t M = (size_t)n * c.seq_len, W = c.width, R = c.mlp_ratio;
+    int rc;
+    if ((rc = dev_alloc(f, &f->r32_a, M * W * 4)) || (rc = dev_alloc(f, &f->r32_qkv, M * 3 * W * 4)) ||
+        (rc = dev_alloc(f, &f->r32_o, M * W * 4)) || (rc = dev_alloc(f, &f->r32_f, M * R * W * 4)))
+        return rc;
+    f->r32_samples = n;
+    return SJD_OK;
+}
+
+// A whole-sequence conditioner pass of a 16-bit flow in float32 arithmetic: the float32 weights of the blob, the
+// float32 kernels, float32 activations in the refinement workspaces.  n <= f->r32_samples.
+void conditioner_pass_f32(sjd_flow *f, int j, const float *x, int n, const int32_t *active, hipStream_t s) {
+    const int dtype = f->cfg.dtype;
+    void *a = f->a, *qkv = f->qkv, *o = f->o, *ff = f->f, *panel = f->arena_panel;
+    f->cfg.dtype = SJD_DTYPE_F32;
+    f->a = f->r32_a; f->qkv = f->r32_qkv; f->o = f->r32_o; f->f = f->r32_f; f->arena_panel = nullptr;
+    conditioner_pass(f, j, x, n, active, s);
+    f->cfg.dtype = dtype;
+    f->a = a; f->qkv = qkv; f->o = o; f->f = ff; f->arena_panel = panel;
+}
+
 int run_jacobi(sjd_flow *f, int j, const float *z, float *x, int batch, const sjd_jacobi_opts *opts, int *passes_out,
                bool *nonfinite_out, hipStream_t s, bool trace = false, const float *x_ref = nullptr) {
     const sjd_config &c = f->cfg;
@@ -423,37 +455,58 @@ int run_jacobi(sjd_flow *f, int j, const float *z, float *x, int batch, const sj
     st.active_in = f->active[0];
     st.active_out = f->active[1];
     launch_jacobi_init(z, x, st, batch, T, D, opts->init, s);
-    int n_live = batch, n_listed = batch, passes = 0;
+    // refinement: a sample marked fine (its delta fell below opts->refine_below) runs in float32 from then on;
+    // the compaction puts those samples at the end of the list
+    const float refine = c.dtype != SJD_DTYPE_F32 ? opts->refine_below : 0.f;
+    if (refine > 0.f) { int rc = ensure_refine_workspace(f); if (rc) return rc; }
+    int n_live = batch, n_listed = batch, n_fine = 0, passes = 0;
     while (n_live > 0 && passes < cap) {
         // Alg. 1 starts every sample from the same iterate, x^0 = 0, and the conditioner sees nothing else: the
         // parameters of the first pass are the same for all samples.  That pass therefore runs on the rows of one
         // sample (sample 0, still all zero) and its head output serves the whole batch - the same bits as running
         // it on every sample, since a row's result does not depend on which other rows are in the pass.
         const bool shared_first = passes == 0 && opts->init == 0 && n_listed > 1;
-        if (shared_first) conditioner_pass(f, j, x, 1, nullptr, s);
-        else conditioner_pass(f, j, x, n_listed, st.active_in, s);
-        {
-            ProfScope ps(f, SJD_PROF_EPILOGUE, 0.0, (double)n_listed * T * D * 24.0, s);
-            launch_jacobi_epilogue(f->p, z, x, st, n_listed, T, D, rev, opts->tau, opts->criterion, cap,
-                                   opts->drop_converged, shared_first ? 1 : 0, s);
+        auto update = [&](JacobiState part, int n, int shared) {
+            ProfScope ps(f, SJD_PROF_EPILOGUE, 0.0, (double)n * T * D * 24.0, s);
+            launch_jacobi_update(f->p, z, x, part, n, T, D, rev, opts->tau, opts->criterion, cap, shared, refine, s);
+        };
+        if (shared_first) {
+            conditioner_pass(f, j, x, 1, nullptr, s);
+            update(st, n_listed, 1);
+        } else {
+            const int n16 = n_listed - n_fine;
+            if (n16 > 0) {
+                conditioner_pass(f, j, x, n16, st.active_in, s);
+                update(st, n16, 0);
+            }
+            for (int off = n16; off < n_listed; off += f->r32_samples) {
+                const int n = n_listed - off < f->r32_samples ? n_listed - off : f->r32_samples;
+                JacobiState part = st;
+                part.active_in = st.active_in + off;
+                conditioner_pass_f32(f, j, x, n, part.active_in, s);
+                update(part, n, 0);
+            }
         }
+        launch_jacobi_compact(st, n_listed, opts->drop_converged ? 0 : 1, s);
         if (trace)
             launch_jacobi_trace(x, x_ref, st, f->trace + (size_t)passes * batch,
                                 f->trace + ((size_t)T + passes) * batch, batch, T, D, s);
-        HIP_TRY(hipMemcpyAsync(f->host_pin, st.n_active_out, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipMemcpyAsync(f->host_pin, st.n_active_out, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
         HIP_TRY(hipStreamSynchronize(s));
         HIP_TRY(hipGetLastError());
         n_live = f->host_pin[0];
-        if (n_live < 0 || n_live > batch) return fail(SJD_EHIP, "active-sample count %d is out of range", n_live);
+        n_fine = f->host_pin[1];
+        if (n_live < 0 || n_live > batch || n_fine < 0 || n_fine > n_live)
+            return fail(SJD_EHIP, "active-sample counts %d, %d are out of range", n_live, n_fine);
         if (opts->drop_converged) n_listed = n_live;
         int32_t *t = st.active_in; st.active_in = st.active_out; st.active_out = t;
         ++passes;
     }
-    HIP_TRY(hipMemcpyAsync(f->host_pin + 1, st.nonfinite, sizeof(int32_t), hipMemcpyDeviceToHost, s));
-    HIP_TRY(hipMemcpyAsync(f->host_pin + 2, st.iters, sizeof(int32_t) * batch, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipMemcpyAsync(f->host_pin + 2, st.nonfinite, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipMemcpyAsync(f->host_pin + 3, st.iters, sizeof(int32_t) * batch, hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
     *passes_out = passes;
-    *nonfinite_out = f->host_pin[1] != 0;
+    *nonfinite_out = f->host_pin[2] != 0;
     return SJD_OK;
 }
 
@@ -707,7 +760,8 @@ int sjd_flow_create(const sjd_config *cfg, sjd_flow **out) {
     A((void **)&f->st.iters, B * 4);
     A((void **)&f->st.done, B * 4);
     A((void **)&f->st.nonfinite, 4);
-    A((void **)&f->st.n_active_out, 4);
+    A((void **)&f->st.n_active_out, 8);
+    A((void **)&f->st.fine, B * 4);
     A((void **)&f->active[0], B * 4);
     A((void **)&f->active[1], B * 4);
     A((void **)&f->trace, 2 * T * B * 4);
@@ -725,7 +779,7 @@ int sjd_flow_create(const sjd_config *cfg, sjd_flow **out) {
     if (rc == SJD_OK && hipMemset(f->ticket, 0, 4) != hipSuccess) rc = fail(SJD_EHIP, "hipMemset failed");
     if (rc == SJD_OK && hipStreamCreateWithFlags(&f->cap_stream, hipStreamNonBlocking) != hipSuccess)
         rc = fail(SJD_EHIP, "hipStreamCreate failed");
-    if (rc == SJD_OK && hipHostMalloc((void **)&f->host_pin, (B + 2) * sizeof(int32_t)) != hipSuccess)
+    if (rc == SJD_OK && hipHostMalloc((void **)&f->host_pin, (B + 3) * sizeof(int32_t)) != hipSuccess)
         rc = fail(SJD_ENOMEM, "pinned host allocation failed");
     for (int i = 0; rc == SJD_OK && i <= c.n_blocks; ++i)
         if (hipEventCreate(&f->ev[i]) != hipSuccess) rc = fail(SJD_EHIP, "hipEventCreate failed");
@@ -873,7 +927,7 @@ int sjd_jacobi_inverse_block(sjd_flow *f, int block, const float *z_dev, float *
     int passes = 0;
     bool nonfinite = false;
     if ((rc = run_jacobi(f, block, z_dev, x_dev, batch, opts, &passes, &nonfinite, s))) return rc;
-    if (iters_per_sample_host) memcpy(iters_per_sample_host, f->host_pin + 2, sizeof(int32_t) * batch);
+    if (iters_per_sample_host) memcpy(iters_per_sample_host, f->host_pin + 3, sizeof(int32_t) * batch);
     if (block_iters_host) *block_iters_host = passes;
     if (nonfinite) return fail(SJD_ENONFINITE, "block %d: a sample ended with a non-finite difference norm", block);
     return SJD_OK;
@@ -915,8 +969,8 @@ int sjd_sample(sjd_flow *f, const float *z_dev, float *x_dev, int batch, uint32_
             if ((rc = run_jacobi(f, j, in, out, batch, opts, &passes, &nonfinite, s))) return rc;
             any_nonfinite |= nonfinite;
             double sum = 0;
-            for (int b = 0; b < batch; ++b) sum += f->host_pin[2 + b];
-            if (iters_host) memcpy(iters_host + (size_t)j * batch, f->host_pin + 2, sizeof(int32_t) * batch);
+            for (int b = 0; b < batch; ++b) sum += f->host_pin[3 + b];
+            if (iters_host) memcpy(iters_host + (size_t)j * batch, f->host_pin + 3, sizeof(int32_t) * batch);
             if (stats_host) {
                 stats_host->block_iters[j] = passes;
                 stats_host->mean_sample_iters[j] = batch ? (float)(sum / batch) : 0.f;
@@ -959,7 +1013,7 @@ int sjd_jacobi_trace_block(sjd_flow *f, int block, const float *z_dev, float *x_
         HIP_TRY(hipStreamSynchronize(s));
     }
     if (block_iters_host) *block_iters_host = passes;
-    if (iters_per_sample_host) memcpy(iters_per_sample_host, f->host_pin + 2, sizeof(int32_t) * batch);
+    if (iters_per_sample_host) memcpy(iters_per_sample_host, f->host_pin + 3, sizeof(int32_t) * batch);
     if (nonfinite) return fail(SJD_ENONFINITE, "block %d: a sample ended with a non-finite difference norm", block);
     return SJD_OK;
 }

@@ -8,6 +8,8 @@ The record these tests pin (measured on the MI355X):
   IEEE half       err 3e-3                err 2e-3, oracle's counts      err 3e-3, 59..79 passes (oracle 8..10)
   bf16 operands   err 2.3e-2 (> 2e-2)     err 2e-2, 21..41 passes        230..235 passes of 256
 
+  half + float32 refinement below 1e-3 (sjd_jacobi_opts.refine_below):            err 3e-3, oracle's counts (+-1)
+
 Every 16-bit operand is a rounding stage; Jacobi decoding iterates the map, so once the true change of
 an iterate is below the rounding noise of one pass the difference norm stays at that noise: about 1.4e-4
 (mean |dx|) with IEEE-half operands and 1.1e-3 with bf16 operands.  A threshold under the floor is only
@@ -38,13 +40,13 @@ def c2(orc32):
     return cfg, blob, z, torch.from_numpy(z).cuda(), full, ref
 
 
-def _run(c2, dtype, tau):
+def _run(c2, dtype, tau, **opts):
     import paper_2505_24791_amd as sjd
     cfg, blob, z, zd, full, ref = c2
     f = sjd.Flow(cfg, max_batch=NB, dtype=dtype)
     f.load_weights(blob)
     xs, _, _ = f.sample(zd, 0, sjd.JacobiOpts(tau=tau))
-    xj, _, iters = f.sample(zd, ~1 & full, sjd.JacobiOpts(tau=tau))
+    xj, _, iters = f.sample(zd, ~1 & full, sjd.JacobiOpts(tau=tau, **opts))
     f.close()
     err_seq = float(np.abs(xs.cpu().numpy() - ref["seq"]).max())
     err_sel = float(np.abs(xj.cpu().numpy() - ref[tau][0]).max())
@@ -87,3 +89,32 @@ def test_bf16_operands_miss_the_sample_bound_and_the_counts_at_workload_scale(c2
     # the difference norm floors near tau: two to five times the oracle's passes
     assert (iters[1:] >= riters[1:]).all()
     assert iters[1:].min() >= 2 * riters[1:].max(), "bf16 counts came close to the oracle's: revisit the record"
+
+
+def test_half_mode_with_float32_refinement_follows_the_oracle_counts_under_the_floor(c2):
+    """tau = 1e-4 lies under the rounding floor of half operands.  With refine_below = 1e-3 a sample's passes run
+    in float32 once its delta is under 1e-3: the float32 passes contract the rounding noise of the half passes
+    away like any other error of the iterate, and the sample stops within one pass of exact arithmetic."""
+    err_seq, err_sel, iters, riters, rdel = _run(c2, 2, 1e-4, refine_below=1e-3)
+    print(f"IEEE half + float32 below 1e-3, tau 1e-4: err {err_sel:.2e}, passes {iters[1:].tolist()} "
+          f"(oracle {riters[1:].tolist()})")
+    assert err_sel <= 2e-2
+    ok = _not_knife_edge(rdel, 1e-4)
+    assert (np.abs(iters.astype(int) - riters)[ok] <= 1).all()
+
+
+def test_refinement_is_per_sample(c2):
+    """A sample switches to float32 by its own delta, so its result and count do not depend on the batch it runs
+    in: each sample alone gives the bits it gives inside the batch."""
+    import torch
+    import paper_2505_24791_amd as sjd
+    cfg, blob, z, zd, full, ref = c2
+    f = sjd.Flow(cfg, max_batch=NB, dtype=2)
+    f.load_weights(blob)
+    opts = sjd.JacobiOpts(tau=1e-4, refine_below=1e-3)
+    y = f.sequential_inverse_block(0, zd)
+    xb, itb, _, _ = f.jacobi_inverse_block(1, y, opts)
+    for b in (0, NB - 1):
+        x1, it1, _, _ = f.jacobi_inverse_block(1, y[b:b + 1].contiguous(), opts)
+        assert torch.equal(x1[0], xb[b]) and int(it1[0]) == int(itb[b])
+    f.close()
