@@ -235,11 +235,13 @@ SJD_API int sjd_op_panel_linear_h16_noalloc(int dtype, const void *a_dev, const 
                                             int M, int N, int K, int epilogue, void *hip_stream);
 
 /* Whole-sequence causal multi-head attention of the conditioner on its own (the attention inside s_k, g_k of
- * eq. 5, evaluated for all positions at once as in the map F of Def. A.1), head size 64, in a 16-bit mode;
- * exported so that the matrix-core attention kernel can be checked against the oracle at any token count.
- * qkv_dev: DEVICE, [n_samples * T, 3 * H * 64] 16-bit row-major, columns [q | k | v], head h owning columns
- * 64 h .. 64 h + 63 of each group.  o_dev: DEVICE, [n_samples * T, H * 64] 16-bit, position t attending
- * positions 0..t with scale 1/8.  No T x T buffer is formed.  SJD_EINVAL for non-positive sizes or T > 4096. */
+ * eq. 5, evaluated for all positions at once as in the map F of Def. A.1), head size 64, in the mode `dtype`
+ * (the 16-bit modes, or SJD_DTYPE_F32 for the float32 kernel that refined passes and float32 flows use);
+ * exported so that the matrix-core attention kernels can be checked against the oracle at any token count.
+ * qkv_dev: DEVICE, [n_samples * T, 3 * H * 64] row-major in that type, columns [q | k | v], head h owning
+ * columns 64 h .. 64 h + 63 of each group.  o_dev: DEVICE, [n_samples * T, H * 64] in that type, position t
+ * attending positions 0..t with scale 1/8.  No T x T buffer is formed.  SJD_EINVAL for non-positive sizes or
+ * T > 4096. */
 SJD_API int sjd_op_attention_h16(int dtype, const void *qkv_dev, void *o_dev, int n_samples, int T, int H,
                                  void *hip_stream);
 

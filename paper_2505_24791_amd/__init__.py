@@ -177,13 +177,12 @@ def op_panel_linear_h16(a, wt, bias, M, N, epilogue, *, K=512, ln_g=None, ln_b=N
 
 
 def op_attention_h16(qkv, n_samples, T, H):
-    """``sjd_op_attention_h16`` on a torch tensor: qkv [n_samples*T, 3*H*64] float16 or bfloat16; returns o
-    [n_samples*T, H*64] of the same type."""
+    """``sjd_op_attention_h16`` on a torch tensor: qkv [n_samples*T, 3*H*64] float16, bfloat16 or float32;
+    returns o [n_samples*T, H*64] of the same type."""
     import torch
     lib = load_library()
     assert qkv.is_cuda and qkv.is_contiguous() and tuple(qkv.shape) == (n_samples * T, 3 * H * 64)
-    assert qkv.dtype in (torch.float16, torch.bfloat16)
-    dtype = DTYPE_F16 if qkv.dtype == torch.float16 else DTYPE_BF16
+    dtype = {torch.float16: DTYPE_F16, torch.bfloat16: DTYPE_BF16, torch.float32: DTYPE_F32}[qkv.dtype]
     o = torch.empty((n_samples * T, H * 64), dtype=qkv.dtype, device=qkv.device)
     _check(lib.sjd_op_attention_h16(dtype, C.c_void_p(qkv.data_ptr()), C.c_void_p(o.data_ptr()), n_samples, T, H,
                                     _stream_ptr()))

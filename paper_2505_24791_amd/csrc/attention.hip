@@ -319,4 +319,175 @@ void launch_flash_attention_h16(const HT *qkv, HT *o, int n_samples, int T, int 
 template void launch_flash_attention_h16<bf16>(const bf16 *, bf16 *, int, int, int, hipStream_t);
 template void launch_flash_attention_h16<f16>(const f16 *, f16 *, int, int, int, hipStream_t);
 
+// ------------------------------------------------------------------------------------------------
+// The same scheme in float32 (head size 64) on the 32x32x2 float32 matrix instruction: a lane feeds ONE
+// value per operand and instruction (lane half g = index g of the contracted pair).  The order in which the
+// contracted index is walked is free as long as both operands agree, which removes every transposition:
+//   S^T = K Q^T : step s of half g stands for d = 32 g + s, so a lane's 32 values of Q are one contiguous half
+//                 row (registers), and its values of K four at a time a 16-byte LDS read;
+//   O^T += V^T P^T : step s of half g stands for key 8 (s / 4) + 4 g + s % 4 of the 32-key block, which is
+//                 exactly the key whose probability sits in accumulator register s of that lane half; V is
+//                 read row-major, 32 consecutive d per half wave.
+// LDS: K [64 keys][64 d], 16-byte chunk c of row `key` in slot c ^ fb_kswz(key) (the 16 lanes of one pass of a
+// 16-byte read - lanes that agree in bits 3 and 5 - are rows {0-7, 16-23} or {8-15, 24-31} of a 32-key block
+// and land on 16 different slots); V [64 keys][64 d], column col of row `key` at col ^ 32 (key / 4 % 2), so the two
+// halves of a wave (keys 4 apart) read different halves of the banks.
+constexpr int FB_BQ = 128, FB_BK = 64, FB_DH = 64;
+__device__ __forceinline__ int fb_kswz(int key) { return (key & 7) | (((key >> 4) & 1) << 3); }
+
+__global__ __launch_bounds__(256, 2) void flash_attention_f32_kernel(const float *__restrict__ qkv, float *__restrict__ o,
+                                                                  int T, int H, int n_pairs, float scale_log2) {
+    __shared__ __attribute__((aligned(16))) float Ks[FB_BK * FB_DH];
+    __shared__ __attribute__((aligned(16))) float Vs[FB_BK * FB_DH];
+    const int W = H * FB_DH;
+    const int n_qt = (T + FB_BQ - 1) / FB_BQ;
+    // the query tiles of one (sample, head) take consecutive slots of one XCD (see the 16-bit kernel)
+    const int slot = (int)blockIdx.x >> 3;
+    const int pair = (slot / n_qt) * 8 + ((int)blockIdx.x & 7);
+    if (pair >= n_pairs) return;
+    const int qt = n_qt - 1 - slot % n_qt;
+    const int h = pair % H, i = pair / H;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, g = lane >> 5;
+    const float *base = qkv + (size_t)i * T * 3 * W;
+    const int q0 = qt * FB_BQ + wave * 32;
+    const int qrow = q0 + l32;
+    const int qrow_c = qrow < T ? qrow : T - 1;
+
+    float qf[32];                                  // Q[qrow][32 g + s]
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const f32x4 t = *reinterpret_cast<const f32x4 *>(base + (size_t)qrow_c * 3 * W + h * FB_DH + 32 * g + 4 * j);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) qf[4 * j + e] = t[e];
+    }
+    f32x16 oacc[2];
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) oacc[db][v] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    const int last_row = min(qt * FB_BQ + FB_BQ - 1, T - 1);
+    const int n_kt = last_row / FB_BK + 1;
+    f32x4 kreg[4], vreg[4];
+    auto fetch_tile = [&](int kt_) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int c = tid + r * 256;
+            const int key = c >> 4, ch = c & 15;
+            int krow = kt_ * FB_BK + key;
+            krow = krow < T ? krow : T - 1;
+            const float *src = base + (size_t)krow * 3 * W + h * FB_DH + ch * 4;
+            kreg[r] = *reinterpret_cast<const f32x4 *>(src + W);
+            vreg[r] = *reinterpret_cast<const f32x4 *>(src + 2 * W);
+        }
+    };
+    fetch_tile(0);
+    for (int kt = 0; kt < n_kt; ++kt) {
+        const int key0 = kt * FB_BK;
+        __syncthreads();  // previous tile fully consumed
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int c = tid + r * 256;
+            const int key = c >> 4, ch = c & 15;
+            *reinterpret_cast<f32x4 *>(&Ks[key * FB_DH + ((ch ^ fb_kswz(key)) << 2)]) = kreg[r];
+            *reinterpret_cast<f32x4 *>(&Vs[key * FB_DH + ((ch ^ (((key >> 2) & 1) << 3)) << 2)]) = vreg[r];
+        }
+        __syncthreads();
+        if (kt + 1 < n_kt) fetch_tile(kt + 1);
+        if (key0 > q0 + 31) continue;  // tile lies entirely above this wave's rows (wave-uniform)
+
+        f32x16 sacc[2];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sacc[kb][v] = 0.f;
+            const int key = 32 * kb + l32;
+#pragma unroll
+            for (int s4 = 0; s4 < 8; ++s4) {
+                const f32x4 kf = *reinterpret_cast<const f32x4 *>(&Ks[key * FB_DH + (((8 * g + s4) ^ fb_kswz(key)) << 2)]);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x2f32(kf[e], qf[4 * s4 + e], sacc[kb], 0, 0, 0);
+            }
+        }
+        // register v of block kb is key key0 + 32 kb + 8 (v/4) + 4 g + v%4, query qrow
+        const bool diag = key0 + FB_BK - 1 > q0;
+        float mx = -INFINITY;
+        if (diag) {
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int key = key0 + 32 * kb + 8 * (v >> 2) + 4 * g + (v & 3);
+                    const float sv = key <= qrow ? sacc[kb][v] : -INFINITY;
+                    sacc[kb][v] = sv;
+                    mx = fmaxf(mx, sv);
+                }
+        } else {
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sacc[kb][v]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;
+        const float m_new = fmaxf(m_run, mx);
+        const float m_use = m_new == -INFINITY ? 0.f : m_new;   // rows past the end of the sequence stay finite
+        const float corr = exp2f(m_run - m_use);
+        float psum = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const float pv = exp2f(fmaf(sacc[kb][v], scale_log2, -m_use));
+                sacc[kb][v] = pv;
+                psum += pv;
+            }
+        psum += __shfl_xor(psum, 32, 64);
+        l_run = l_run * corr + psum;
+        m_run = m_new;
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) oacc[db][v] *= corr;
+
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int s = 0; s < 16; ++s) {
+                const int key = 32 * kb + 8 * (s >> 2) + 4 * g + (s & 3);
+#pragma unroll
+                for (int db = 0; db < 2; ++db) {
+                    const float vf = Vs[key * FB_DH + ((32 * db + l32) ^ (g << 5))];
+                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x2f32(vf, sacc[kb][s], oacc[db], 0, 0, 0);
+                }
+            }
+    }
+    // O^T block db: register v is d = 32 db + 8 (v/4) + 4 g + v%4, query qrow
+    if (qrow < T) {
+        const float inv = 1.0f / l_run;
+        float *orow = o + ((size_t)i * T + qrow) * W + h * FB_DH;
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                f32x4 ov;
+#pragma unroll
+                for (int b = 0; b < 4; ++b) ov[b] = oacc[db][4 * a + b] * inv;
+                *reinterpret_cast<f32x4 *>(orow + 32 * db + 8 * a + 4 * g) = ov;
+            }
+    }
+}
+
+void launch_flash_attention_f32(const float *qkv, float *o, int n_samples, int T, int H, hipStream_t s) {
+    if (n_samples <= 0) return;
+    const int n_qt = (T + FB_BQ - 1) / FB_BQ;
+    const float scale_log2 = 1.4426950408889634f / sqrtf((float)FB_DH);
+    const int n_pairs = n_samples * H;
+    const unsigned grid = (unsigned)((n_pairs + 7) / 8) * 8u * (unsigned)n_qt;
+    hipLaunchKernelGGL(flash_attention_f32_kernel, dim3(grid), dim3(256), 0, s, qkv, o, T, H, n_pairs, scale_log2);
+}
+
+
 }  // namespace sjd

@@ -192,6 +192,8 @@ void launch_decode_attention(const AT *qkv, AT *kcache, AT *vcache, AT *o, int B
 // Flash-style causal attention on 16-bit qkv [n_samples*T, 3W] (head size 64), o [n_samples*T, W].
 template <typename HT>
 void launch_flash_attention_h16(const HT *qkv, HT *o, int n_samples, int T, int H, hipStream_t s);
+// the same in float32 (float32 matrix instruction), head size 64
+void launch_flash_attention_f32(const float *qkv, float *o, int n_samples, int T, int H, hipStream_t s);
 
 // Skinny 16-bit projection for single-token steps (M <= 256 rows, K % 32 == 0); same contract as
 // launch_gemm_h16.

@@ -288,6 +288,8 @@ void attention_full(const void *qkv, void *o, int n, int T, int W, int H, int ma
     const AT *q = (const AT *)qkv;
     if constexpr (sizeof(AT) == 2) {
         if (W / H == 64 && mask_o == 0) { launch_flash_attention_h16<AT>(q, (AT *)o, n, T, H, s); return; }
+    } else {
+        if (W / H == 64 && mask_o == 0) { launch_flash_attention_f32(q, (float *)o, n, T, H, s); return; }
     }
     // the masked probe (a diagnostic) takes the row-wise kernel in every mode
     launch_attention_rows<AT, AT>(q, 3 * W, q + W, q + 2 * W, 3 * W, (int64_t)T * 3 * W, (AT *)o, W, n, T, 0, H, W / H,
@@ -1179,11 +1181,12 @@ int sjd_op_panel_linear_h16_noalloc(int dtype, const void *a_dev, const float *l
 
 int sjd_op_attention_h16(int dtype, const void *qkv_dev, void *o_dev, int n_samples, int T, int H, void *hip_stream) {
     if (!qkv_dev || !o_dev) return fail(SJD_EINVAL, "null device pointer");
-    if (dtype != SJD_DTYPE_BF16 && dtype != SJD_DTYPE_F16) return fail(SJD_EINVAL, "dtype must be a 16-bit mode");
+    if (dtype != SJD_DTYPE_BF16 && dtype != SJD_DTYPE_F16 && dtype != SJD_DTYPE_F32) return fail(SJD_EINVAL, "unknown dtype %d", dtype);
     if (n_samples < 1 || T < 1 || T > 4096 || H < 1 || H > 65535 || n_samples > 65535)
         return fail(SJD_EINVAL, "need 1 <= n_samples, H <= 65535 and 1 <= T <= 4096");
     hipStream_t s = (hipStream_t)hip_stream;
-    if (dtype == SJD_DTYPE_BF16) launch_flash_attention_h16<bf16>((const bf16 *)qkv_dev, (bf16 *)o_dev, n_samples, T, H, s);
+    if (dtype == SJD_DTYPE_F32) launch_flash_attention_f32((const float *)qkv_dev, (float *)o_dev, n_samples, T, H, s);
+    else if (dtype == SJD_DTYPE_BF16) launch_flash_attention_h16<bf16>((const bf16 *)qkv_dev, (bf16 *)o_dev, n_samples, T, H, s);
     else launch_flash_attention_h16<f16>((const f16 *)qkv_dev, (f16 *)o_dev, n_samples, T, H, s);
     HIP_TRY(hipStreamSynchronize(s));
     HIP_TRY(hipGetLastError());

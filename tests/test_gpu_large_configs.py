@@ -194,3 +194,20 @@ def test_flash_attention_long_sequence_matches_oracle(torch_cuda, orc64, dtype_n
         ref = orc64.causal_attention(q32[i, :, :W], q32[i, :, W:2 * W], q32[i, :, 2 * W:], H)
         # probabilities are rounded to 16 bits before the second product: relative 2^-11 (2^-8) per term
         assert np.abs(o[i] - ref).max() <= 4 * out_eps * np.abs(q32[i, :, 2 * W:]).max(), (T, dtype_name, i)
+
+
+@pytest.mark.parametrize("T", [1024, 1000, 257, 40])
+def test_flash_attention_float32_matches_oracle(torch_cuda, orc64, T):
+    """The float32 attention kernel (float32 matrix instruction; refined passes of 16-bit flows and float32
+    flows with head size 64) against the oracle's attention: float32 accumulation error only."""
+    import paper_2505_24791_amd as sjd
+    torch = torch_cuda
+    n, H = 2, 3
+    W = H * 64
+    g = np.random.default_rng(100 + T)
+    qkv = g.standard_normal((n * T, 3 * W)).astype(np.float32)
+    o = sjd.op_attention_h16(torch.from_numpy(qkv).cuda(), n, T, H).cpu().numpy().reshape(n, T, W)
+    q3 = qkv.reshape(n, T, 3 * W)
+    for i in range(n):
+        ref = orc64.causal_attention(q3[i, :, :W], q3[i, :, W:2 * W], q3[i, :, 2 * W:], H)
+        assert np.abs(o[i] - ref).max() <= 2e-5 * np.abs(q3[i, :, 2 * W:]).max(), (T, i)

@@ -62,6 +62,9 @@ F32_CASES = [
                              batch=7, bf16=False), True),
     ("one_token", wl.FlowConfig("one_token", n_blocks=2, n_layers=1, width=32, n_heads=2, seq_len=1, token_dim=4,
                                 batch=3, bf16=False), True),
+    # head size 64: whole-sequence attention runs on the float32 matrix-instruction kernel (two query tiles, ragged)
+    ("dh64", wl.FlowConfig("dh64", n_blocks=2, n_layers=2, width=128, n_heads=2, seq_len=150, token_dim=6,
+                           batch=3, bf16=False), True),
 ]
 
 
