@@ -5,8 +5,10 @@
 //    whole-sequence passes and, with a key/value cache, every single-token step of the sequential
 //    inverse (Sec. 3.5), where it is bound by reading the cached prefix from HBM.
 //  * flash_attention_h16_kernel: whole-sequence causal attention for head size 64 on 16-bit data with
-//    MFMA; K tiles and transposed V tiles are staged in LDS, scores never leave registers
-//    (online softmax in float32), so there is no T x T buffer.
+//    MFMA; K and V tiles are staged in LDS, scores never leave registers (online softmax in float32), so
+//    there is no T x T buffer.
+//  * flash_attention_f32_kernel: the same in float32 on the float32 matrix instruction (float32 flows and
+//    the refined passes of 16-bit flows).
 #include "common.h"
 
 namespace sjd {
@@ -130,25 +132,42 @@ template void launch_decode_attention<f16>(const f16 *, f16 *, f16 *, f16 *, int
 // S^T = K Q^T, so that a lane holds one query column: row statistics of the online softmax are
 // lane-local plus one cross-half exchange, and the probabilities are already laid out as the
 // B operand of the second product O^T = V^T P^T (16 keys per instruction).
+// K/V tiles of 64 keys are double-buffered in LDS (one barrier per tile; the next tile's rows are on their
+// way into registers while the current one is used) and consumed in two steps of 32 keys, each a complete
+// step of the online softmax; the accumulator is rescaled only when some row's running maximum moved.
+// 121 registers: four workgroups per CU.
+//
+// The two 32-lane halves of a wave exchange a value in one instruction (v_permlane32_swap with both operands
+// the same register): every lane gets the value of its position in the lower half and in the upper half.
+__device__ __forceinline__ void wave_halves(float x, float &lower, float &upper) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    lower = __uint_as_float(r[0]);
+    upper = __uint_as_float(r[1]);
+}
 constexpr int FA_BQ = 128, FA_BK = 64, FA_DH = 64;
 // LDS tiles are swizzled instead of padded.  K [key][d]: the 16-byte chunk c of row `key` sits in slot
 // c ^ (bits 1, 2 and 4 of key): a 16-byte read of a wave is served in four passes of 16 lanes (lanes
 // that agree in bits 3 and 5) over 64 banks, and the 16 rows of a pass - {0-7, 16-23} or {8-15, 24-31}
-// of a 32-key block - then fall on 16 different 16-byte bank groups (8 (key & 1) + slot).  V^T [d][key]:
-// key column k of row d sits at k ^ (((d >> 3) & 7) << 2): the eight rows d = 8 dc + e that one
-// transposing store instruction touches, and the rows a fragment read touches, spread over the banks,
-// while groups of four consecutive keys stay contiguous.
+// of a 32-key block - then fall on 16 different 16-byte bank groups (8 (key & 1) + slot).
 constexpr int FA_KS = FA_DH;       // K tile row stride (elements)
 __device__ __forceinline__ int fa_kswz(int key) { return ((key >> 1) & 3) | (((key >> 4) & 1) << 2); }
-constexpr int FA_VS = FA_BK;       // V^T tile row stride (elements)
+// V stays row-major in LDS (16-byte stores, no transposition on the way in) and the V^T fragments of the second
+// product come out of the transposing 64-bit LDS read of gfx950, which works on groups of 16 lanes: output lane
+// j of a group receives element (j % 4) of source lanes (j / 4) + 4 t, t = 0..3.  With source lane s pointing at
+// row (s / 4), columns 4 (s % 4) .. + 3 of a 4 x 16 block of V (4 keys, 16 values of d), output lane j holds the
+// four keys of column j: the k-contiguous piece of the A operand of O^T += V^T P^T for d = that column.
+// V [key][d]: the 16-byte chunk c of row `key` sits in slot c ^ (4 (key / 2 % 2)): the four rows that a 16-lane
+// group reads (128 bytes apart: rows of equal parity start on the same bank) then use disjoint bank groups
+// (the LDS bank-conflict counter reads zero on this kernel).
+typedef short i16x4 __attribute__((ext_vector_type(4)));
 
 template <typename HT>
-__global__ __launch_bounds__(256, 2) void flash_attention_h16_kernel(const HT *__restrict__ qkv, HT *__restrict__ o,
-                                                                  int T, int H, int n_pairs, float scale_log2) {
+__global__ __launch_bounds__(256, 4) void flash_attention_h16_kernel(const HT *__restrict__ qkv, HT *__restrict__ o,
+                                                                     int T, int H, int n_pairs, float scale_log2) {
     typedef typename Half16<HT>::v8 v8;
     typedef typename Half16<HT>::v4 v4;
-    __shared__ __attribute__((aligned(16))) HT Ks[FA_BK * FA_KS];
-    __shared__ __attribute__((aligned(16))) HT Vt[FA_DH * FA_VS];
+    __shared__ __attribute__((aligned(16))) HT Ks[2][FA_BK * FA_KS];
+    __shared__ __attribute__((aligned(16))) HT Vs[2][FA_BK * FA_DH];
     const int W = H * FA_DH;
     const int n_qt = (T + FA_BQ - 1) / FA_BQ;
     // Workgroups go to the eight XCDs round robin by their linear index, and each XCD has an L2 of its own:
@@ -162,11 +181,10 @@ __global__ __launch_bounds__(256, 2) void flash_attention_h16_kernel(const HT *_
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, g = lane >> 5;
     const HT *base = qkv + (size_t)i * T * 3 * W;
-    const int q0 = qt * FA_BQ + wave * 32;      // first query row of this wave
-    const int qrow = q0 + l32;                  // this lane's query row
+    const int q0 = qt * FA_BQ + wave * 32;
+    const int qrow = q0 + l32;
     const int qrow_c = qrow < T ? qrow : T - 1;
 
-    // Q^T as B operand: lane (q = l32, g) holds Q[q][16c + 8g .. +7] for the four 16-wide chunks of dh
     v8 qf[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c)
@@ -178,11 +196,24 @@ __global__ __launch_bounds__(256, 2) void flash_attention_h16_kernel(const HT *_
 #pragma unroll
         for (int v = 0; v < 16; ++v) oacc[db][v] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
+    // Q has to have arrived before the loop: otherwise the compiler, which cannot tell a first iteration from a
+    // later one, waits for Q inside the loop by waiting for every younger load - the K/V loads of the next tile
+    // that were issued a moment before - and the prefetch is lost.
+    asm volatile("" :: "v"(qf[0]), "v"(qf[1]), "v"(qf[2]), "v"(qf[3]));
+
+    // this lane's part of a transposing read: source row (4 g + j16 / 4) of the 8-key group, the 8-byte piece
+    // (j16 % 4) of the 32 bytes that hold d = 32 db + 16 hh .. + 15, chunk slot swizzled by the row
+    const int j16 = lane & 15, hh = (lane >> 4) & 1;
+    int voff[2];                                 // element offsets inside a V tile, for db = 0, 1
+#pragma unroll
+    for (int db = 0; db < 2; ++db) {
+        const int chunk = 4 * db + 2 * hh + ((j16 & 3) >> 1);
+        const int slot_v = chunk ^ (((j16 >> 3) & 1) << 2);
+        voff[db] = (4 * g + (j16 >> 2)) * FA_DH + slot_v * 8 + (j16 & 1) * 4;
+    }
 
     const int last_row = min(qt * FA_BQ + FA_BQ - 1, T - 1);
     const int n_kt = last_row / FA_BK + 1;
-    // K/V tiles go global -> registers -> LDS; the registers of tile kt+1 are requested before tile kt is
-    // used, so that their latency hides behind the matrix instructions of tile kt.
     v8 kreg[2], vreg[2];
     auto fetch_tile = [&](int kt_) {
 #pragma unroll
@@ -196,102 +227,100 @@ __global__ __launch_bounds__(256, 2) void flash_attention_h16_kernel(const HT *_
             vreg[r] = *reinterpret_cast<const v8 *>(src + 2 * W);
         }
     };
-    fetch_tile(0);
-    for (int kt = 0; kt < n_kt; ++kt) {
-        const int key0 = kt * FA_BK;
-        __syncthreads();  // previous tile fully consumed
-        // stage K [64 keys][64 d] and V^T [64 d][64 keys]; 512 16-byte chunks each, 2 per thread
+    auto stage_tile = [&](int buf) {
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
             const int c = tid + r * 256;
             const int key = c >> 3, dc = c & 7;
-            *reinterpret_cast<v8 *>(&Ks[key * FA_KS + ((dc ^ fa_kswz(key)) << 3)]) = kreg[r];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) Vt[(dc * 8 + e) * FA_VS + (key ^ (dc << 2))] = vreg[r][e];
+            *reinterpret_cast<v8 *>(&Ks[buf][key * FA_KS + ((dc ^ fa_kswz(key)) << 3)]) = kreg[r];
+            *reinterpret_cast<v8 *>(&Vs[buf][key * FA_DH + ((dc ^ (((key >> 1) & 1) << 2)) << 3)]) = vreg[r];
         }
-        __syncthreads();
+    };
+    fetch_tile(0);
+    stage_tile(0);
+    __syncthreads();
+    for (int kt = 0; kt < n_kt; ++kt) {
+        const int key0 = kt * FA_BK, buf = kt & 1;
         if (kt + 1 < n_kt) fetch_tile(kt + 1);
-        if (key0 > q0 + 31) continue;  // tile lies entirely above this wave's rows (wave-uniform)
-
-        // S^T = K Q^T : two 32-key blocks
-        f32x16 sacc[2];
+        const HT *Kt = Ks[buf], *Vt = Vs[buf];
+        // the tile in two steps of 32 keys, each a complete step of the online softmax (16 accumulator registers
+        // of scores instead of 32); a 32-key block that lies entirely above this wave's rows is skipped
+        // (wave-uniform test)
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
+            const int kb0 = key0 + 32 * kb;
+            if (kb0 > q0 + 31) continue;
+            f32x16 sacc;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) sacc[kb][v] = 0.f;
+            for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                const v8 kf = *reinterpret_cast<const v8 *>(&Ks[(32 * kb + l32) * FA_KS + (((2 * c + g) ^ fa_kswz(l32)) << 3)]);
-                sacc[kb] = Half16<HT>::mfma(kf, qf[c], sacc[kb]);
+                const v8 kf = *reinterpret_cast<const v8 *>(&Kt[(32 * kb + l32) * FA_KS + (((2 * c + g) ^ fa_kswz(l32)) << 3)]);
+                sacc = Half16<HT>::mfma(kf, qf[c], sacc);
             }
-        }
-        // register v of block kb is key key0 + 32 kb + 8 (v/4) + 4 g + v%4, query qrow.  Only tiles that
-        // reach the diagonal need the causal mask (wave-uniform test); scores stay unscaled, the softmax
-        // scale (times log2 e) enters through one fused multiply-add in front of the exponential.
-        const bool diag = key0 + FA_BK - 1 > q0;
-        float mx = -INFINITY;
-        if (diag) {
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+            // register v is key kb0 + 8 (v/4) + 4 g + v%4, query qrow; only blocks that reach the diagonal need
+            // the causal mask; scores stay unscaled, the softmax scale (times log2 e) enters through one fused
+            // multiply-add in front of the exponential
+            float mx = -INFINITY;
+            if (kb0 + 31 > q0) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int key = key0 + 32 * kb + 8 * (v >> 2) + 4 * g + (v & 3);
-                    const float sv = key <= qrow ? sacc[kb][v] : -INFINITY;
-                    sacc[kb][v] = sv;
+                    const int key = kb0 + 8 * (v >> 2) + 4 * g + (v & 3);
+                    const float sv = key <= qrow ? sacc[v] : -INFINITY;
+                    sacc[v] = sv;
                     mx = fmaxf(mx, sv);
                 }
-        } else {
+            } else {
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+                for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sacc[v]);
+            }
+            { float lo, hi; wave_halves(mx, lo, hi); mx = fmaxf(lo, hi) * scale_log2; }   // scale > 0: the maximum commutes with it
+            const float m_new = fmaxf(m_run, mx);
+            // rows past the end of the sequence may see no visible key; keep them finite
+            const float m_use = m_new == -INFINITY ? 0.f : m_new;
+            // a row whose maximum did not move has the factor exp2(0) = 1: when that holds for every row of the
+            // wave the rescaling is skipped, with the same bits
+            if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {
+                const float corr = __builtin_amdgcn_exp2f(m_run - m_use);
+                l_run *= corr;
 #pragma unroll
-                for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sacc[kb][v]);
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;     // scale > 0: the maximum commutes with it
-        const float m_new = fmaxf(m_run, mx);
-        // rows past the end of the sequence may see no visible key in a tile; keep them finite
-        const float m_use = m_new == -INFINITY ? 0.f : m_new;
-        const float corr = __builtin_amdgcn_exp2f(m_run - m_use);
-        float psum = 0.f;
+                for (int db = 0; db < 2; ++db)
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+                    for (int v = 0; v < 16; ++v) oacc[db][v] *= corr;
+                m_run = m_new;
+            }
+            float psum = 0.f;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const float pv = __builtin_amdgcn_exp2f(fmaf(sacc[kb][v], scale_log2, -m_use));
-                sacc[kb][v] = pv;
+                const float pv = __builtin_amdgcn_exp2f(fmaf(sacc[v], scale_log2, -m_use));
+                sacc[v] = pv;
                 psum += pv;
             }
-        psum += __shfl_xor(psum, 32, 64);
-        l_run = l_run * corr + psum;
-        m_run = m_new;
-#pragma unroll
-        for (int db = 0; db < 2; ++db)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) oacc[db][v] *= corr;
+            { float lo, hi; wave_halves(psum, lo, hi); l_run += lo + hi; }
 
-        // O^T += V^T P^T, 16 keys per instruction.  Slot e = 4a + b of lane half g stands for key
-        // 32 kb + 16 c2 + 8 a + 4 g + b in both operands.
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+            // O^T += V^T P^T, 16 keys per instruction.  Slot e = 4 a + b of lane half g stands for key
+            // kb0 + 16 c2 + 8 a + 4 g + b in both operands.
 #pragma unroll
             for (int c2 = 0; c2 < 2; ++c2) {
                 v8 pf;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) pf[e] = from_f32<HT>(sacc[kb][8 * c2 + e]);
+                for (int e = 0; e < 8; ++e) pf[e] = from_f32<HT>(sacc[8 * c2 + e]);
 #pragma unroll
                 for (int db = 0; db < 2; ++db) {
-                    const int vsw = (((l32 >> 3) & 3) | (db << 2)) << 2;           // ((d >> 3) & 7) << 2 for d = 32 db + l32
-                    const int kcol = 32 * kb + 16 * c2 + 4 * g;
-                    const HT *vrow = &Vt[(32 * db + l32) * FA_VS];
-                    const v4 lo = *reinterpret_cast<const v4 *>(vrow + (kcol ^ vsw));
-                    const v4 hi = *reinterpret_cast<const v4 *>(vrow + ((kcol + 8) ^ vsw));
+                    union { i16x4 r; v4 h; } lo, hi;
+                    const HT *vp = Vt + (32 * kb + 16 * c2) * FA_DH + voff[db];
+                    lo.r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)(vp));
+                    hi.r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)(vp + 8 * FA_DH));
                     v8 vf;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) { vf[e] = lo[e]; vf[4 + e] = hi[e]; }
+                    for (int e = 0; e < 4; ++e) { vf[e] = lo.h[e]; vf[4 + e] = hi.h[e]; }
                     oacc[db] = Half16<HT>::mfma(vf, pf, oacc[db]);
                 }
             }
+        }
+        if (kt + 1 < n_kt) stage_tile(buf ^ 1);   // last read before the previous barrier
+        __syncthreads();
     }
-    // O^T block db: register v is d = 32 db + 8 (v/4) + 4 g + v%4, query qrow
     if (qrow < T) {
         const float inv = 1.0f / l_run;
         HT *orow = o + ((size_t)i * T + qrow) * W + h * FA_DH;
@@ -367,6 +396,9 @@ __global__ __launch_bounds__(256, 2) void flash_attention_f32_kernel(const float
 #pragma unroll
         for (int v = 0; v < 16; ++v) oacc[db][v] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
+    // Q in registers before the loop (see the 16-bit kernel: the loop would otherwise wait for its own prefetch)
+#pragma unroll
+    for (int j = 0; j < 32; j += 4) asm volatile("" :: "v"(qf[j]), "v"(qf[j + 1]), "v"(qf[j + 2]), "v"(qf[j + 3]));
 
     const int last_row = min(qt * FB_BQ + FB_BQ - 1, T - 1);
     const int n_kt = last_row / FB_BK + 1;
@@ -431,7 +463,7 @@ __global__ __launch_bounds__(256, 2) void flash_attention_f32_kernel(const float
 #pragma unroll
                 for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sacc[kb][v]);
         }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;
+        { float lo, hi; wave_halves(mx, lo, hi); mx = fmaxf(lo, hi) * scale_log2; }
         const float m_new = fmaxf(m_run, mx);
         const float m_use = m_new == -INFINITY ? 0.f : m_new;   // rows past the end of the sequence stay finite
         const float corr = exp2f(m_run - m_use);
@@ -444,7 +476,7 @@ __global__ __launch_bounds__(256, 2) void flash_attention_f32_kernel(const float
                 sacc[kb][v] = pv;
                 psum += pv;
             }
-        psum += __shfl_xor(psum, 32, 64);
+        { float lo, hi; wave_halves(psum, lo, hi); psum = lo + hi; }
         l_run = l_run * corr + psum;
         m_run = m_new;
 #pragma unroll
