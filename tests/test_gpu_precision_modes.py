@@ -117,6 +117,9 @@ def test_refinement_is_per_sample(c2):
     for b in (0, NB - 1):
         x1, it1, _, _ = f.jacobi_inverse_block(1, y[b:b + 1].contiguous(), opts)
         assert torch.equal(x1[0], xb[b]) and int(it1[0]) == int(itb[b])
+    # keeping converged samples in the batch changes neither results nor counts
+    xk, itk, _, _ = f.jacobi_inverse_block(1, y, sjd.JacobiOpts(tau=1e-4, refine_below=1e-3, drop_converged=0))
+    assert torch.equal(xk, xb) and np.array_equal(itk, itb)
     f.close()
 
 
