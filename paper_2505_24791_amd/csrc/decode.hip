@@ -339,7 +339,13 @@ static void launch_skinny_epi(const HT *A, const HT *Wt, const float *bias, cons
     // instructions, which is what a launch of this size needs.  Row-major operands: waves split the
     // rows and a workgroup owns 32 columns.
     if (frag) {
-        if (M <= 32) launch_skinny_cfg<HT, 2, 1, 16, true, true, EPI, OutT>(A, Wt, bias, resid, C, M, N, K, s);
+        // A long k with few columns (the MLP output at width 1024: 64 column blocks, each workgroup reading all of
+        // the [M, 4096] activation) leaves three quarters of the CUs idle, and the activation is most of what a
+        // workgroup reads: there, 16 rows per workgroup and two workgroups per column block (both on the same XCD:
+        // the weight slice comes from memory once).  Same bits: a row's sum does not depend on the rows beside it.
+        if (M > 16 && M <= 32 && K >= 2048 && N <= 1024)
+            launch_skinny_cfg<HT, 1, 1, 16, true, true, EPI, OutT>(A, Wt, bias, resid, C, M, N, K, s);
+        else if (M <= 32) launch_skinny_cfg<HT, 2, 1, 16, true, true, EPI, OutT>(A, Wt, bias, resid, C, M, N, K, s);
         else launch_skinny_cfg<HT, 4, 1, 8, true, true, EPI, OutT>(A, Wt, bias, resid, C, M, N, K, s);
     } else if (M <= 128) {
         launch_skinny_cfg<HT, 2, 2, 4, false, false, EPI, OutT>(A, Wt, bias, resid, C, M, N, K, s);
