@@ -215,16 +215,33 @@ __global__ __launch_bounds__(256, 4) void flash_attention_h16_kernel(const HT *_
     const int last_row = min(qt * FA_BQ + FA_BQ - 1, T - 1);
     const int n_kt = last_row / FA_BK + 1;
     v8 kreg[2], vreg[2];
-    auto fetch_tile = [&](int kt_) {
+    // a thread's two 16-byte pieces of a tile: a wave-uniform tile base plus an offset that does not change from
+    // tile to tile; only a last tile that reaches past the sequence clamps its rows (wave-uniform branch)
+    uint32_t koff[2];
 #pragma unroll
-        for (int r = 0; r < 2; ++r) {
-            const int c = tid + r * 256;
-            const int key = c >> 3, dc = c & 7;
-            int krow = kt_ * FA_BK + key;
-            krow = krow < T ? krow : T - 1;
-            const HT *src = base + (size_t)krow * 3 * W + h * FA_DH + dc * 8;
-            kreg[r] = *reinterpret_cast<const v8 *>(src + W);
-            vreg[r] = *reinterpret_cast<const v8 *>(src + 2 * W);
+    for (int r = 0; r < 2; ++r) {
+        const int c = tid + r * 256;
+        koff[r] = (uint32_t)(((c >> 3) * 3 * W + h * FA_DH + (c & 7) * 8 + W) * (int)sizeof(HT));
+    }
+    auto fetch_tile = [&](int kt_) {
+        if ((kt_ + 1) * FA_BK <= T) {
+            const char *tb = reinterpret_cast<const char *>(base + (size_t)kt_ * FA_BK * 3 * W);
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                kreg[r] = *reinterpret_cast<const v8 *>(tb + koff[r]);
+                vreg[r] = *reinterpret_cast<const v8 *>(tb + koff[r] + (size_t)W * sizeof(HT));
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                const int c = tid + r * 256;
+                const int key = c >> 3, dc = c & 7;
+                int krow = kt_ * FA_BK + key;
+                krow = krow < T ? krow : T - 1;
+                const HT *src = base + (size_t)krow * 3 * W + h * FA_DH + dc * 8;
+                kreg[r] = *reinterpret_cast<const v8 *>(src + W);
+                vreg[r] = *reinterpret_cast<const v8 *>(src + 2 * W);
+            }
         }
     };
     auto stage_tile = [&](int buf) {
@@ -289,14 +306,11 @@ __global__ __launch_bounds__(256, 4) void flash_attention_h16_kernel(const HT *_
                     for (int v = 0; v < 16; ++v) oacc[db][v] *= corr;
                 m_run = m_new;
             }
-            float psum = 0.f;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const float pv = __builtin_amdgcn_exp2f(fmaf(sacc[v], scale_log2, -m_use));
-                sacc[v] = pv;
-                psum += pv;
-            }
-            { float lo, hi; wave_halves(psum, lo, hi); l_run += lo + hi; }
+            for (int v = 0; v < 16; ++v) sacc[v] = __builtin_amdgcn_exp2f(fmaf(sacc[v], scale_log2, -m_use));
+            // the row sum is taken over the probabilities as they enter the second product (rounded to 16 bits),
+            // two per instruction, in float32
+            float psum = 0.f;
 
             // O^T += V^T P^T, 16 keys per instruction.  Slot e = 4 a + b of lane half g stands for key
             // kb0 + 16 c2 + 8 a + 4 g + b in both operands.
@@ -305,6 +319,7 @@ __global__ __launch_bounds__(256, 4) void flash_attention_h16_kernel(const HT *_
                 v8 pf;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) pf[e] = from_f32<HT>(sacc[8 * c2 + e]);
+                psum = Half16<HT>::add_all(pf, psum);
 #pragma unroll
                 for (int db = 0; db < 2; ++db) {
                     union { i16x4 r; v4 h; } lo, hi;
@@ -317,6 +332,7 @@ __global__ __launch_bounds__(256, 4) void flash_attention_h16_kernel(const HT *_
                     oacc[db] = Half16<HT>::mfma(vf, pf, oacc[db]);
                 }
             }
+            { float lo, hi; wave_halves(psum, lo, hi); l_run += lo + hi; }
         }
         if (kt + 1 < n_kt) stage_tile(buf ^ 1);   // last read before the previous barrier
         __syncthreads();

@@ -46,12 +46,29 @@ template <> struct Half16<bf16> {
     static __device__ __forceinline__ f32x16 mfma(v8 a, v8 b, f32x16 c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
     }
+    // c + the sum of the eight values of p, in float32 (two values per instruction)
+    static __device__ __forceinline__ float add_all(v8 p, float c) {
+        typedef __bf16 v2 __attribute__((ext_vector_type(2)));
+        const v2 one = {(__bf16)1.f, (__bf16)1.f};
+        c = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(p, p, 0, 1), one, c, false);
+        c = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(p, p, 2, 3), one, c, false);
+        c = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(p, p, 4, 5), one, c, false);
+        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(p, p, 6, 7), one, c, false);
+    }
 };
 template <> struct Half16<f16> {
     typedef f16x4 v4;
     typedef f16x8 v8;
     static __device__ __forceinline__ f32x16 mfma(v8 a, v8 b, f32x16 c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ float add_all(v8 p, float c) {
+        typedef _Float16 v2 __attribute__((ext_vector_type(2)));
+        const v2 one = {(_Float16)1.f, (_Float16)1.f};
+        c = __builtin_amdgcn_fdot2(__builtin_shufflevector(p, p, 0, 1), one, c, false);
+        c = __builtin_amdgcn_fdot2(__builtin_shufflevector(p, p, 2, 3), one, c, false);
+        c = __builtin_amdgcn_fdot2(__builtin_shufflevector(p, p, 4, 5), one, c, false);
+        return __builtin_amdgcn_fdot2(__builtin_shufflevector(p, p, 6, 7), one, c, false);
     }
 };
 
