@@ -141,6 +141,32 @@ def test_config4_all_jacobi_matches_oracle(torch_cuda, orc32):
     f.close()
 
 
+def test_config5_refined_passes_follow_the_oracle_under_the_floor(torch_cuda, orc32):
+    """Configuration 5's smallest threshold, tau = 1e-4, lies under the rounding floor of half operands; with
+    refine_below = 1e-3 a sample's last passes run in float32 (float32 attention over 1024 tokens, float32
+    projections at k = 1024 and 4096) and its count is the oracle's or one more.  Two blocks, full batch on
+    the GPU, the oracle on a spread of samples."""
+    import paper_2505_24791_amd as sjd
+    torch = torch_cuda
+    cfg = wl.CONFIGS["C5"].with_(n_blocks=2)
+    blob = wl.make_weights(cfg)
+    z = wl.make_latent(cfg)
+    tau = 1e-4
+    f = sjd.Flow(cfg)
+    f.load_weights(blob)
+    x, stats, iters = f.sample(_dev(torch, z), 0b10, sjd.JacobiOpts(tau=tau, refine_below=1e-3))
+    print(f"C5 refined: GPU passes per block {stats['block_iters']}, ms per block {[round(v, 1) for v in stats['block_ms']]}",
+          flush=True)
+    picks = _spread(cfg.batch, 4)
+    rx, riters, rdel = orc32.sample(cfg, blob, z[picks], 0b10, tau)
+    err = float(np.abs(x.cpu().numpy()[picks] - rx).max())
+    print(f"C5 refined: max |err| {err:.3e}; passes gpu {iters[1, picks].tolist()} oracle {riters[1].tolist()}", flush=True)
+    assert err <= TOL_16BIT
+    _compare_counts("C5 refined", iters[:, picks], riters, rdel, tau)
+    assert (iters[1] < 40).all(), "no sample may sit on the rounding floor"
+    f.close()
+
+
 # ------------------------------------------------------------------------------------------------
 # op level: the projection tiles at the long k of the MLP output, flash attention at T = 1024
 
